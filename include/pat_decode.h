@@ -1,0 +1,211 @@
+/*
+ * pat_decode.h -- C ABI of the single-GPU decode-step library (libpat_decode.so).
+ *
+ * What it is: the decode step that the paper's inference executor repeats once
+ * per generated token during the generation stage (Sec. 2.1), on ONE GPU's
+ * tensor-parallel shard (Sec. 3.1: a TP degree shards weights and KV states, so
+ * a shard is a set of shapes: heads/tp, ffn/tp, vocab/tp), while finished
+ * sequences leave the live batch (Sec. 3.2), and the (batch, context length)
+ * -> step latency table that the paper's offline profiler produces for its
+ * latency predictor (Sec. 4.1, "Offline Profiler").
+ *
+ * Conventions
+ *  - Every call returns PAT_OK (0) or a negative error; nothing is thrown or
+ *    aborted.  On error no state is changed.  pat_last_error() gives the text.
+ *  - "device" pointers are GPU global memory of the current HIP device; "host"
+ *    pointers are ordinary process memory.  The library allocates NO device
+ *    memory: the caller allocates the three arenas pat_decode_query() sizes
+ *    (256-byte aligned) and keeps them alive until pat_decode_destroy().
+ *  - All GPU work is enqueued on the stream given to pat_decode_init().  Calls
+ *    are asynchronous with respect to the host unless stated.
+ *  - One context must not be used from two host threads at once.
+ *  - Tensors are row-major; weights and cached K/V are bf16, activations and
+ *    logits fp32, integer state int32.
+ */
+#ifndef PAT_DECODE_H
+#define PAT_DECODE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PAT_OK       0
+#define PAT_EINVAL  (-1)   /* bad argument, shape not divisible by tp, limit exceeded */
+#define PAT_ENOMEM  (-2)   /* KV pages / token budget / batch slots exhausted */
+#define PAT_ESTATE  (-3)   /* call order (weights not loaded, empty batch, ...) */
+#define PAT_EHIP    (-4)   /* a HIP runtime call failed */
+
+typedef struct pat_ctx pat_ctx;
+
+/* FULL-model dimensions plus which tensor-parallel shard this GPU holds
+ * (Sec. 3.1).  Shard shapes: hq = n_q_heads/tp, hkv = max(1, n_kv_heads/tp),
+ * F = ffn/tp, Vs = vocab/tp.  Limits: head_dim in {64, 128}; hidden, hq*head_dim
+ * and ffn/tp multiples of 32; vocab/tp a multiple of 16; max_batch <= 1024;
+ * page_tokens in {16, 32, 64, 128}. */
+typedef struct pat_cfg {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int32_t tp_degree, tp_rank;
+    float   rms_eps, rope_base;
+    int32_t max_batch;        /* live-batch slots */
+    int32_t max_seq_len;      /* longest context (prompt + response) of one sequence */
+    int32_t page_tokens;      /* tokens per KV page */
+    int64_t kv_token_budget;  /* active-token capacity of the KV pool: the paper's T_cap (Sec. 4.1) */
+    int32_t eos_token;        /* < 0: sequences end by target length only */
+} pat_cfg;
+
+/* Arena sizes in bytes for a configuration. */
+typedef struct pat_mem_req {
+    int64_t weights_bytes;    /* packed weights of all layers + embedding + head */
+    int64_t kv_bytes;         /* paged K/V pool, all layers */
+    int64_t work_bytes;       /* activations, attention partials, tables, integer state */
+    int32_t n_pages;          /* pages in the pool = ceil(budget/page_tokens) + max_batch */
+    int32_t max_pages_per_seq;
+} pat_mem_req;
+
+typedef struct pat_buffers {  /* device arenas, 256-byte aligned, sizes from pat_decode_query */
+    void *weights, *kv, *work;
+} pat_buffers;
+
+/* One layer of this shard, device, row-major bf16:
+ *   g1, g2 [hidden]; wqkv [(hq + 2 hkv) d, hidden] (q rows, k rows, v rows);
+ *   wo [hidden, hq d]; wg, wu [F, hidden]; wd [hidden, F].                      */
+typedef struct pat_layer_weights {
+    const void *g1, *wqkv, *wo, *g2, *wg, *wu, *wd;
+} pat_layer_weights;
+
+/* embed [vocab, hidden] (full table, replicated); gf [hidden]; wlm [Vs, hidden]. */
+typedef struct pat_final_weights {
+    const void *embed, *gf, *wlm;
+} pat_final_weights;
+
+/* What the inference executor reports to the switch controller after a step
+ * (Sec. 4.1: active batch size and current sequence lengths). */
+typedef struct pat_step_report {
+    int32_t live_batch;       /* slots that took part in the step */
+    int32_t n_finished;       /* of those, finished by this step (removed by pat_kv_compact) */
+    int64_t sum_context;      /* T = sum of context lengths after the step */
+    int32_t free_pages;
+    int32_t step_index;
+} pat_step_report;
+
+/* One row of the profile grid (Sec. 4.1: mean of 60 decode steps per (B, L) point,
+ * kept only if B*L <= T_cap). */
+typedef struct pat_grid_row {
+    int32_t tp_degree, batch, kv_len, skipped;   /* skipped: 0 measured, 1 B*L > t_cap, 2 does not fit the pool */
+    int64_t sum_context;                         /* T at the first timed step */
+    double  mean_us, min_us, std_us;             /* over reps of the per-rep mean */
+    double  tokens_per_s;
+    double  algo_bytes;                          /* algorithmic HBM bytes of one step at the window's middle */
+    double  hbm_frac;                            /* algo_bytes / mean time / 8e12 */
+} pat_grid_row;
+
+/* Sizes of the arenas for cfg.  Host only. */
+int pat_decode_query(const pat_cfg *cfg, pat_mem_req *out);
+
+/* Creates a context over caller-allocated arenas; builds the rotary table and
+ * the empty page pool on `hip_stream` (a hipStream_t, may be NULL = default). */
+int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_stream, pat_ctx **out);
+
+/* Copies one layer's / the final tensors into the library's streaming layout
+ * inside the weights arena.  The sources may be freed once the stream has
+ * passed this call.  Every layer and the final tensors must be loaded before
+ * the first step. */
+int pat_load_layer(pat_ctx *ctx, int32_t layer, const pat_layer_weights *w);
+int pat_load_final(pat_ctx *ctx, const pat_final_weights *w);
+
+/* Appends n sequences to the live batch (host arrays of n): id, the token to
+ * feed next, the number of tokens already in its KV cache (their K/V are then
+ * written with pat_kv_write), and the number of tokens to generate.
+ * PAT_ENOMEM if slots, pages or the token budget do not suffice. */
+int pat_decode_admit(pat_ctx *ctx, int32_t n, const int32_t *seq_id, const int32_t *token,
+                     const int32_t *kv_len, const int32_t *target_len);
+
+/* Copies K and V of tokens [0, n_tokens) of live slot `slot`, layer `layer`
+ * between contiguous device buffers [n_tokens, hkv, d] bf16 and the slot's pages. */
+int pat_kv_write(pat_ctx *ctx, int32_t slot, int32_t layer, const void *k_dev, const void *v_dev, int32_t n_tokens);
+int pat_kv_read(pat_ctx *ctx, int32_t slot, int32_t layer, void *k_dev, void *v_dev, int32_t n_tokens);
+
+/* One decode step over the live batch: embedding, n_layers x (RMSNorm, QKV,
+ * rotary + KV append, attention over the paged cache, O + residual, RMSNorm,
+ * gate/up + SiLU*mul, down + residual), final RMSNorm, vocabulary-slice logits,
+ * greedy argmax (lowest index on ties, global id = tp_rank*Vs + local), finish
+ * flags.  The chosen token becomes the slot's next input.
+ *   report_host   NULL, or filled after synchronising the stream;
+ *   next_tok_dev  NULL, or device int32[live] receiving the chosen token ids;
+ *   logits_dev    NULL, or device float[live, Vs] receiving the logits.
+ * Finished slots stay in the batch until pat_kv_compact; stepping with finished
+ * slots present is PAT_ESTATE. */
+int pat_decode_step(pat_ctx *ctx, pat_step_report *report_host, int32_t *next_tok_dev, float *logits_dev);
+
+/* Removes finished slots on the device: survivors keep their order, their
+ * per-slot state and page-table rows move down, finished slots' pages return
+ * to the pool.  No K/V payload moves.  new_live_host (may be NULL) receives the
+ * new batch size. */
+int pat_kv_compact(pat_ctx *ctx, int32_t *new_live_host);
+
+/* Copies the live slots' integer state to host arrays (each NULL or [live]).
+ * Synchronises the stream. */
+int pat_get_state(pat_ctx *ctx, int32_t *live, int32_t *seq_id, int32_t *token, int32_t *kv_len,
+                  int32_t *gen, int32_t *target, int32_t *fin);
+
+/* Page table rows of the live slots, host int32[live, max_pages_per_seq]
+ * (entries beyond a slot's pages are unspecified), and the free list.
+ * For allocator-invariant tests.  Synchronises. */
+int pat_get_pages(pat_ctx *ctx, int32_t *page_table_host, int32_t *free_list_host, int32_t *n_free);
+
+/* Offline-profiler sweep (Sec. 4.1): for every (batch, kv_len) pair with
+ * batch*kv_len <= t_cap: empties the batch, admits `batch` sequences of
+ * `kv_len` cached tokens with pseudo-random N(0,1)-like K/V, runs `warmup`
+ * untimed and `steps` timed decode steps (HIP events), `reps` times.
+ * rows_out has capacity *n_rows; *n_rows returns the rows written (nb*nl).
+ * Destroys the current live batch.  Synchronous. */
+int pat_profile_grid(pat_ctx *ctx, const int32_t *batches, int32_t nb, const int32_t *kv_lens, int32_t nl,
+                     int64_t t_cap, int32_t steps, int32_t warmup, int32_t reps, uint64_t seed,
+                     pat_grid_row *rows_out, int32_t *n_rows);
+
+/* Drops every live sequence and returns all pages to the pool. */
+int pat_decode_reset(pat_ctx *ctx);
+
+/* Algorithmic HBM bytes of one step for the current live batch (weights once,
+ * K/V of every cached token once, appended K/V), host arithmetic. */
+int pat_step_algo_bytes(pat_ctx *ctx, double *weight_bytes, double *kv_bytes);
+
+/* Kernel-class timing: when enabled, every launch of the class is bracketed by
+ * HIP events on the step's stream; totals accumulate until read.
+ * class: 0 weight-streaming projections, 1 attention (partial + merge), 2 everything else. */
+int pat_timing_enable(pat_ctx *ctx, int32_t on);
+int pat_timing_read(pat_ctx *ctx, int32_t klass, double *total_ms, int64_t *launches, int32_t reset);
+
+int pat_decode_destroy(pat_ctx *ctx);
+const char *pat_last_error(const pat_ctx *ctx);   /* owned by ctx; "" if none */
+
+/* ---- single operators, for kernel-level parity tests and micro-benchmarks ----
+ * All pointers device, work on `hip_stream`, asynchronous.                        */
+
+/* Bytes of the streaming layout of a [n, k] bf16 matrix (n padded to 16). k % 32 == 0. */
+int64_t pat_op_packed_weight_bytes(int32_t n, int32_t k);
+/* w [n, k] row-major bf16 -> streaming layout.  If w2 != NULL, rows of w and w2
+ * (each [n, k]) are interleaved (w row f, w2 row f, ...) into a [2n, k] matrix. */
+int pat_op_pack_weight(const void *w, const void *w2, int32_t n, int32_t k, void *packed, void *hip_stream);
+/* Bytes of ONE of the two packed activation buffers for [b, k] (b padded to 16). */
+int64_t pat_op_packed_act_bytes(int32_t b, int32_t k);
+/* x [b, k] fp32 -> split-bf16 operand buffers (hi = bf16(x), lo = bf16(x - hi)). */
+int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, void *hip_stream);
+/* y [b, n] (+)= x W^T with W in streaming layout.  mode 0: y = ; mode 1: y += ;
+ * mode 2: W is a gate/up interleave of [2f, k]; y_hi/y_lo receive
+ * silu(gate)*up as packed split-bf16 activations [b, f] (y unused). */
+int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b,
+                float *y, int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *hip_stream);
+/* RMSNorm of x [b, h] with gains g [h] bf16 into packed split-bf16 activations. */
+int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo,
+                        void *hip_stream);
+/* (max, lowest index) per row of logits [b, n]; out_idx[b] = base + index. NaN counts as -inf. */
+int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val,
+                  void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAT_DECODE_H */

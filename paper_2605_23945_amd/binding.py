@@ -1,0 +1,320 @@
+"""ctypes binding of libpat_decode.so: same names as include/pat_decode.h.
+
+Argument marshalling only.  torch supplies device memory (the three arenas, the
+staging tensors) and the stream; every step of the decode path runs in the
+library's HIP kernels.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpat_decode.so")
+
+PAT_OK, PAT_EINVAL, PAT_ENOMEM, PAT_ESTATE, PAT_EHIP = 0, -1, -2, -3, -4
+
+
+class PatError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"pat error {code}: {msg}")
+        self.code = code
+
+
+class pat_cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab",
+                                         "tp_degree", "tp_rank")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("max_batch", C.c_int32), ("max_seq_len", C.c_int32), ("page_tokens", C.c_int32),
+                ("kv_token_budget", C.c_int64), ("eos_token", C.c_int32)]
+
+
+class pat_mem_req(C.Structure):
+    _fields_ = [("weights_bytes", C.c_int64), ("kv_bytes", C.c_int64), ("work_bytes", C.c_int64),
+                ("n_pages", C.c_int32), ("max_pages_per_seq", C.c_int32)]
+
+
+class pat_buffers(C.Structure):
+    _fields_ = [("weights", C.c_void_p), ("kv", C.c_void_p), ("work", C.c_void_p)]
+
+
+class pat_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")]
+
+
+class pat_final_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("embed", "gf", "wlm")]
+
+
+class pat_step_report(C.Structure):
+    _fields_ = [("live_batch", C.c_int32), ("n_finished", C.c_int32), ("sum_context", C.c_int64),
+                ("free_pages", C.c_int32), ("step_index", C.c_int32)]
+
+
+class pat_grid_row(C.Structure):
+    _fields_ = [("tp_degree", C.c_int32), ("batch", C.c_int32), ("kv_len", C.c_int32), ("skipped", C.c_int32),
+                ("sum_context", C.c_int64), ("mean_us", C.c_double), ("min_us", C.c_double), ("std_us", C.c_double),
+                ("tokens_per_s", C.c_double), ("algo_bytes", C.c_double), ("hbm_frac", C.c_double)]
+
+
+EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_final", "pat_decode_admit",
+           "pat_kv_write", "pat_kv_read", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
+           "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
+           "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_rmsnorm_pack", "pat_op_argmax"]
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """dlopen the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+    lib.pat_decode_query.argtypes = [C.POINTER(pat_cfg), C.POINTER(pat_mem_req)]
+    lib.pat_decode_init.argtypes = [C.POINTER(pat_cfg), C.POINTER(pat_buffers), vp, C.POINTER(vp)]
+    lib.pat_load_layer.argtypes = [vp, C.c_int32, C.POINTER(pat_layer_weights)]
+    lib.pat_load_final.argtypes = [vp, C.POINTER(pat_final_weights)]
+    lib.pat_decode_admit.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p]
+    lib.pat_kv_write.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
+    lib.pat_kv_read.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
+    lib.pat_decode_step.argtypes = [vp, C.POINTER(pat_step_report), vp, vp]
+    lib.pat_kv_compact.argtypes = [vp, i32p]
+    lib.pat_get_state.argtypes = [vp, i32p] + [i32p] * 6
+    lib.pat_get_pages.argtypes = [vp, i32p, i32p, i32p]
+    lib.pat_profile_grid.argtypes = [vp, i32p, C.c_int32, i32p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_uint64, C.POINTER(pat_grid_row), i32p]
+    lib.pat_decode_reset.argtypes = [vp]
+    lib.pat_step_algo_bytes.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.pat_timing_enable.argtypes = [vp, C.c_int32]
+    lib.pat_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]
+    lib.pat_decode_destroy.argtypes = [vp]
+    lib.pat_last_error.argtypes = [vp]
+    lib.pat_last_error.restype = C.c_char_p
+    lib.pat_op_packed_weight_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.pat_op_packed_weight_bytes.restype = C.c_int64
+    lib.pat_op_packed_act_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.pat_op_packed_act_bytes.restype = C.c_int64
+    lib.pat_op_pack_weight.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp]
+    lib.pat_op_pack_act.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
+    lib.pat_op_gemm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, C.c_int32, vp]
+    lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
+    lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def make_cfg(shard, max_batch, max_seq_len, kv_token_budget, page_tokens=64, eos_token=-1) -> pat_cfg:
+    """pat_cfg from a pat_inputs.ShardShape-like object (fields model.*, tp, rank)."""
+    m = shard.model
+    return pat_cfg(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, shard.tp, shard.rank,
+                   m.rms_eps, m.rope_base, max_batch, max_seq_len, page_tokens, kv_token_budget, eos_token)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+class Decoder:
+    """Owns the arenas (torch uint8 tensors on the current device) and a pat_ctx."""
+
+    def __init__(self, cfg: pat_cfg, device="cuda:0"):
+        import torch
+        self.lib = load_library()
+        self.cfg = cfg
+        self.req = pat_mem_req()
+        rc = self.lib.pat_decode_query(C.byref(cfg), C.byref(self.req))
+        if rc:
+            raise PatError(rc, "pat_decode_query rejected the configuration")
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        alloc = lambda n: torch.empty(int(n) + 256, dtype=torch.uint8, device=self.device)
+        self._w, self._kv, self._work = alloc(self.req.weights_bytes), alloc(self.req.kv_bytes), alloc(self.req.work_bytes)
+        al = lambda t: (t.data_ptr() + 255) // 256 * 256
+        self._bufs = pat_buffers(al(self._w), al(self._kv), al(self._work))
+        self.ctx = C.c_void_p()
+        rc = self.lib.pat_decode_init(C.byref(cfg), C.byref(self._bufs), _stream(), C.byref(self.ctx))
+        if rc:
+            raise PatError(rc, "pat_decode_init failed")
+        tp = cfg.tp_degree
+        self.hq, self.hkv = cfg.n_q_heads // tp, max(1, cfg.n_kv_heads // tp)
+        self.vs, self.d = cfg.vocab // tp, cfg.head_dim
+
+    def _chk(self, rc):
+        if rc:
+            raise PatError(rc, self.lib.pat_last_error(self.ctx).decode())
+
+    def close(self):
+        if self.ctx:
+            self.lib.pat_decode_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- same names as the C ABI ---------------------------------------------------
+    def pat_load_layer(self, layer, w: dict):
+        lw = pat_layer_weights(*[_ptr(w[k]) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")])
+        self._chk(self.lib.pat_load_layer(self.ctx, layer, C.byref(lw)))
+
+    def pat_load_final(self, w: dict):
+        fw = pat_final_weights(_ptr(w["embed"]), _ptr(w["gf"]), _ptr(w["wlm"]))
+        self._chk(self.lib.pat_load_final(self.ctx, C.byref(fw)))
+
+    def pat_decode_admit(self, seq_id, token, kv_len, target):
+        a, ap = _i32(seq_id); b, bp = _i32(token); c, cp = _i32(kv_len); d, dp = _i32(target)
+        self._chk(self.lib.pat_decode_admit(self.ctx, len(a), ap, bp, cp, dp))
+
+    def pat_kv_write(self, slot, layer, k, v):
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        self._chk(self.lib.pat_kv_write(self.ctx, slot, layer, _ptr(k), _ptr(v), k.shape[0]))
+
+    def pat_kv_read(self, slot, layer, n_tokens):
+        import torch
+        k = torch.empty((n_tokens, self.hkv, self.d), dtype=torch.bfloat16, device=self.device)
+        v = torch.empty_like(k)
+        self._chk(self.lib.pat_kv_read(self.ctx, slot, layer, _ptr(k), _ptr(v), n_tokens))
+        return k, v
+
+    def pat_decode_step(self, report=True, next_tok=None, logits=None):
+        rep = pat_step_report()
+        self._chk(self.lib.pat_decode_step(self.ctx, C.byref(rep) if report else None, _ptr(next_tok), _ptr(logits)))
+        return rep if report else None
+
+    def pat_kv_compact(self) -> int:
+        n = C.c_int32()
+        self._chk(self.lib.pat_kv_compact(self.ctx, C.byref(n)))
+        return n.value
+
+    def pat_get_state(self) -> dict:
+        mb = self.cfg.max_batch
+        live = C.c_int32()
+        arrs = {k: np.zeros(mb, np.int32) for k in ("seq_id", "token", "kv_len", "gen", "target", "fin")}
+        ps = [a.ctypes.data_as(C.POINTER(C.c_int32)) for a in arrs.values()]
+        self._chk(self.lib.pat_get_state(self.ctx, C.byref(live), *ps))
+        return {k: v[:live.value].copy() for k, v in arrs.items()} | {"live": live.value}
+
+    def pat_get_pages(self):
+        live = self.pat_get_state()["live"]
+        pt = np.zeros((max(live, 1), self.req.max_pages_per_seq), np.int32)
+        fl = np.zeros(self.req.n_pages, np.int32)
+        nf = C.c_int32()
+        self._chk(self.lib.pat_get_pages(self.ctx, pt.ctypes.data_as(C.POINTER(C.c_int32)),
+                                         fl.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nf)))
+        return pt[:live], fl[:nf.value].copy()
+
+    def pat_profile_grid(self, batches, kv_lens, t_cap, steps=60, warmup=3, reps=5, seed=1):
+        b, bp = _i32(batches); l, lp = _i32(kv_lens)
+        rows = (pat_grid_row * (len(b) * len(l)))()
+        n = C.c_int32(len(b) * len(l))
+        self._chk(self.lib.pat_profile_grid(self.ctx, bp, len(b), lp, len(l), t_cap, steps, warmup, reps, seed, rows,
+                                            C.byref(n)))
+        return [{f: getattr(rows[i], f) for f, _ in pat_grid_row._fields_} for i in range(n.value)]
+
+    def pat_decode_reset(self):
+        self._chk(self.lib.pat_decode_reset(self.ctx))
+
+    def pat_step_algo_bytes(self):
+        w, k = C.c_double(), C.c_double()
+        self._chk(self.lib.pat_step_algo_bytes(self.ctx, C.byref(w), C.byref(k)))
+        return w.value, k.value
+
+    def pat_timing_enable(self, on: bool):
+        self._chk(self.lib.pat_timing_enable(self.ctx, int(on)))
+
+    def pat_timing_read(self, klass, reset=True):
+        ms, n = C.c_double(), C.c_int64()
+        self._chk(self.lib.pat_timing_read(self.ctx, klass, C.byref(ms), C.byref(n), int(reset)))
+        return ms.value, n.value
+
+
+# ---- single operators ------------------------------------------------------------------
+
+def pat_op_pack_weight(w, w2=None):
+    """torch bf16 [n, k] (and optionally a second one to interleave) -> packed uint8 tensor."""
+    import torch
+    lib = load_library()
+    n, k = w.shape
+    rows = 2 * n if w2 is not None else n
+    out = torch.empty(lib.pat_op_packed_weight_bytes(rows, k), dtype=torch.uint8, device=w.device)
+    rc = lib.pat_op_pack_weight(_ptr(w.contiguous()), _ptr(w2.contiguous() if w2 is not None else None), n, k, _ptr(out), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_pack_weight")
+    return out
+
+
+def pat_op_pack_act(x):
+    import torch
+    lib = load_library()
+    b, k = x.shape
+    nbytes = lib.pat_op_packed_act_bytes(b, k)
+    hi = torch.empty(nbytes, dtype=torch.uint8, device=x.device); lo = torch.empty_like(hi)
+    rc = lib.pat_op_pack_act(_ptr(x.contiguous()), b, k, _ptr(hi), _ptr(lo), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_pack_act")
+    return hi, lo
+
+
+def pat_op_gemm(w_packed, n, k, xhi, xlo, b, y=None, mode=0, y_hi=None, y_lo=None):
+    lib = load_library()
+    rc = lib.pat_op_gemm(_ptr(w_packed), n, k, _ptr(xhi), _ptr(xlo), b, _ptr(y), (y.stride(0) if y is not None else 0),
+                         _ptr(y_hi), _ptr(y_lo), mode, _stream())
+    if rc:
+        raise PatError(rc, "pat_op_gemm")
+
+
+def pat_op_rmsnorm_pack(x, g, eps):
+    import torch
+    lib = load_library()
+    b, h = x.shape
+    nbytes = lib.pat_op_packed_act_bytes(b, h)
+    hi = torch.empty(nbytes, dtype=torch.uint8, device=x.device); lo = torch.empty_like(hi)
+    rc = lib.pat_op_rmsnorm_pack(_ptr(x.contiguous()), _ptr(g), b, h, eps, _ptr(hi), _ptr(lo), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_rmsnorm_pack")
+    return hi, lo
+
+
+def pat_op_argmax(logits, base=0):
+    import torch
+    lib = load_library()
+    b, n = logits.shape
+    idx = torch.empty(b, dtype=torch.int32, device=logits.device)
+    val = torch.empty(b, dtype=torch.float32, device=logits.device)
+    rc = lib.pat_op_argmax(_ptr(logits.contiguous()), b, n, base, _ptr(idx), _ptr(val), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_argmax")
+    return idx, val
+
+
+def unpack_act(hi, lo, b, k):
+    """Inverse of the packed activation layout (test helper: pure index arithmetic on the host).
+
+    Returns float64 numpy [b, k] = hi + lo.
+    """
+    import torch
+    KS = k // 32
+    bt = (b + 15) // 16
+    def one(t):
+        a = t.view(torch.bfloat16).float().cpu().numpy().reshape(bt, KS, 4, 16, 8)   # [tile, ks, g, r, j]
+        return a.transpose(0, 3, 1, 2, 4).reshape(bt * 16, k)[:b].astype(np.float64)
+    return one(hi) + one(lo)

@@ -1,0 +1,253 @@
+// Split-KV decode attention over the ragged, paged bf16 cache.
+//
+// Work item = (sequence, chunk of up to `chunk_tokens` cached positions, KV head).
+// The flat item list covers the whole live batch, so one long sequence on a
+// shard with a single KV head still spreads over the chip, and neighbouring
+// items read neighbouring heads of the same pages.  A workgroup streams the
+// chunk's K rows (16-byte vectors, one token row = D/8 lanes), keeps the scores
+// of the G query heads that share this KV head in LDS, takes the chunk maximum,
+// then streams V once, accumulating exp(s - m) * V in registers.  It emits the
+// partial (m, l, acc); a second kernel merges a sequence's partials with the
+// online-softmax identity in chunk order, so the result is run-to-run identical.
+#include "pat_dev.h"
+#include "pat_kernels.h"
+
+namespace pat {
+
+namespace {
+
+constexpr int kAttnThreads = 256;
+constexpr int kMaxChunk = 256;
+
+__device__ __forceinline__ int find_slot(const int32_t *chunk_start, int B, int ce)
+{
+    int lo = 0, hi = B;   // largest b with chunk_start[b] <= ce
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (chunk_start[mid] <= ce) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
+{
+    constexpr int LPT = D / 8;                  // lanes per token row
+    constexpr int TPR = kAttnThreads / LPT;     // token rows per round of the workgroup
+    constexpr int UR = 4;                       // rounds in flight
+    __shared__ float sc[G * kMaxChunk];
+    __shared__ float red[4 * G * D];
+    __shared__ float ml[2 * G];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ts = tid / LPT, seg = tid % LPT;
+    const int hkv = a.kv.hkv, P = a.kv.P, C = a.chunk_tokens;
+    const float scale = rsqrtf((float)D);
+    const uint16_t *kbase = a.kv.pool + a.kv.base(a.layer, 0);
+    const uint16_t *vbase = a.kv.pool + a.kv.base(a.layer, 1);
+    const int64_t page_elems = a.kv.page_elems();
+
+    for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+        const int ce = item / hkv, h = item - ce * hkv;
+        const int b = find_slot(a.chunk_start, a.B, ce);
+        const int c = ce - a.chunk_start[b];
+        const int n = a.kv_len[b] + 1;
+        const int t0 = c * C;
+        const int cnt = min(n - t0, C);
+        const int32_t *pt = a.page_table + (int64_t)b * a.max_pages;
+        const int64_t head_off = (int64_t)h * P * D + seg * 8;
+
+        float q[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + g) * D + seg * 8;
+            const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+            const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+            q[g][0] = q0.x; q[g][1] = q0.y; q[g][2] = q0.z; q[g][3] = q0.w;
+            q[g][4] = q1.x; q[g][5] = q1.y; q[g][6] = q1.z; q[g][7] = q1.w;
+        }
+
+        // ---- scores of the chunk ----
+        for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
+            uint4 kv[UR];
+            bool ok[UR];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const int tl = r0 + u * TPR + ts;
+                ok[u] = tl < cnt;
+                kv[u] = make_uint4(0, 0, 0, 0);
+                if (ok[u]) {
+                    const int t = t0 + tl;
+                    const int page = pt[t / P];
+                    kv[u] = *reinterpret_cast<const uint4 *>(kbase + page * page_elems + head_off + (int64_t)(t % P) * D);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const float k0 = bf16lo(kv[u].x), k1 = bf16hi(kv[u].x), k2 = bf16lo(kv[u].y), k3 = bf16hi(kv[u].y);
+                const float k4 = bf16lo(kv[u].z), k5 = bf16hi(kv[u].z), k6 = bf16lo(kv[u].w), k7 = bf16hi(kv[u].w);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float s = q[g][0] * k0;
+                    s = fmaf(q[g][1], k1, s); s = fmaf(q[g][2], k2, s); s = fmaf(q[g][3], k3, s);
+                    s = fmaf(q[g][4], k4, s); s = fmaf(q[g][5], k5, s); s = fmaf(q[g][6], k6, s);
+                    s = fmaf(q[g][7], k7, s);
+#pragma unroll
+                    for (int o = LPT / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+                    if (seg == 0 && ok[u]) sc[g * kMaxChunk + r0 + u * TPR + ts] = s * scale;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- chunk maximum, probabilities, their sum (one wave per query head) ----
+        for (int g = wave; g < G; g += 4) {
+            float m = -INFINITY;
+            for (int t = lane; t < cnt; t += 64) m = fmaxf(m, sc[g * kMaxChunk + t]);
+            m = wave_max(m);
+            float l = 0.f;
+            for (int t = lane; t < cnt; t += 64) {
+                const float p = expf(sc[g * kMaxChunk + t] - m);
+                sc[g * kMaxChunk + t] = p;
+                l += p;
+            }
+            l = wave_sum(l);
+            if (lane == 0) { ml[2 * g] = m; ml[2 * g + 1] = l; }
+        }
+        __syncthreads();
+
+        // ---- sum_t p_t V_t ----
+        float acc[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
+        for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
+            uint4 kv[UR];
+            bool ok[UR];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const int tl = r0 + u * TPR + ts;
+                ok[u] = tl < cnt;
+                kv[u] = make_uint4(0, 0, 0, 0);
+                if (ok[u]) {
+                    const int t = t0 + tl;
+                    const int page = pt[t / P];
+                    kv[u] = *reinterpret_cast<const uint4 *>(vbase + page * page_elems + head_off + (int64_t)(t % P) * D);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                if (!ok[u]) continue;
+                const float v0 = bf16lo(kv[u].x), v1 = bf16hi(kv[u].x), v2 = bf16lo(kv[u].y), v3 = bf16hi(kv[u].y);
+                const float v4 = bf16lo(kv[u].z), v5 = bf16hi(kv[u].z), v6 = bf16lo(kv[u].w), v7 = bf16hi(kv[u].w);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float p = sc[g * kMaxChunk + r0 + u * TPR + ts];
+                    acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
+                    acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
+                    acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
+                    acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
+                }
+            }
+        }
+        // token rows of one wave share `seg` at lane distance LPT, 2 LPT, ...
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float v = acc[g][j];
+#pragma unroll
+                for (int o = 32; o >= LPT; o >>= 1) v += __shfl_xor(v, o, 64);
+                acc[g][j] = v;
+            }
+        if (lane < LPT) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) red[(wave * G + g) * D + lane * 8 + j] = acc[g][j];
+        }
+        __syncthreads();
+        for (int e = tid; e < G * D; e += kAttnThreads) {
+            const int g = e / D, dd = e - g * D;
+            const float v = (red[(0 * G + g) * D + dd] + red[(1 * G + g) * D + dd]) +
+                            (red[(2 * G + g) * D + dd] + red[(3 * G + g) * D + dd]);
+            a.part_acc[((int64_t)ce * a.hq + h * G + g) * D + dd] = v;
+        }
+        if (tid < 2 * G) a.part_ml[((int64_t)ce * a.hq + h * G) * 2 + tid] = ml[tid];
+        __syncthreads();
+    }
+}
+
+// One workgroup per sequence: merge its chunk partials head by head and write
+// the attention output as packed split-bf16 activations for the O projection.
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+{
+    constexpr int LPT = D / 8;
+    const int b = blockIdx.x;
+    const int ce0 = a.chunk_start[b], nch = a.chunk_start[b + 1] - ce0;
+    const int KS = a.hq * D / 32;
+    for (int idx = threadIdx.x; idx < a.hq * LPT; idx += blockDim.x) {
+        const int head = idx / LPT, seg = idx - head * LPT;
+        float M = -INFINITY;
+        for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((int64_t)(ce0 + c) * a.hq + head) * 2]);
+        float den = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < nch; ++c) {
+            const float *mlp = a.part_ml + ((int64_t)(ce0 + c) * a.hq + head) * 2;
+            const float w = expf(mlp[0] - M);
+            den = fmaf(w, mlp[1], den);
+            const float *ap = a.part_acc + ((int64_t)(ce0 + c) * a.hq + head) * D + seg * 8;
+            const float4 p0 = *reinterpret_cast<const float4 *>(ap);
+            const float4 p1 = *reinterpret_cast<const float4 *>(ap + 4);
+            o[0] = fmaf(w, p0.x, o[0]); o[1] = fmaf(w, p0.y, o[1]); o[2] = fmaf(w, p0.z, o[2]); o[3] = fmaf(w, p0.w, o[3]);
+            o[4] = fmaf(w, p1.x, o[4]); o[5] = fmaf(w, p1.y, o[5]); o[6] = fmaf(w, p1.z, o[6]); o[7] = fmaf(w, p1.w, o[7]);
+        }
+        const float inv = 1.0f / den;
+        uint16_t hh[8], ll[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) split_bf16(o[j] * inv, hh[j], ll[j]);
+        const int64_t vi = packed_elem_offset(b, head * D + seg * 8, KS) >> 3;
+        a.ohi[vi] = make_uint4(hh[0] | (uint32_t)hh[1] << 16, hh[2] | (uint32_t)hh[3] << 16,
+                               hh[4] | (uint32_t)hh[5] << 16, hh[6] | (uint32_t)hh[7] << 16);
+        a.olo[vi] = make_uint4(ll[0] | (uint32_t)ll[1] << 16, ll[2] | (uint32_t)ll[3] << 16,
+                               ll[4] | (uint32_t)ll[5] << 16, ll[6] | (uint32_t)ll[7] << 16);
+    }
+}
+
+template <int D>
+hipError_t launch_partial_d(const AttnArgs &a, int grid, hipStream_t s)
+{
+    const int G = a.hq / a.kv.hkv;
+    switch (G) {
+    case 1: attn_partial_kernel<D, 1><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 2: attn_partial_kernel<D, 2><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 4: attn_partial_kernel<D, 4><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 8: attn_partial_kernel<D, 8><<<grid, kAttnThreads, 0, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s)
+{
+    if (a.n_items <= 0) return hipSuccess;
+    if (a.chunk_tokens > kMaxChunk || a.chunk_tokens <= 0) return hipErrorInvalidValue;
+    const int grid = a.n_items < 4096 ? a.n_items : 4096;
+    if (a.kv.d == 128) return launch_partial_d<128>(a, grid, s);
+    if (a.kv.d == 64) return launch_partial_d<64>(a, grid, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s)
+{
+    if (a.B <= 0) return hipSuccess;
+    if (a.kv.d == 128) attn_merge_kernel<128><<<a.B, 256, 0, s>>>(a);
+    else if (a.kv.d == 64) attn_merge_kernel<64><<<a.B, 256, 0, s>>>(a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace pat

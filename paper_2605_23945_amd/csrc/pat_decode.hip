@@ -1,0 +1,706 @@
+// Host side of libpat_decode.so: the C ABI declared in include/pat_decode.h.
+// Validates shapes, carves the caller's arenas, keeps an exact host mirror of the
+// live batch's integer state (lengths, targets, page counts) so that capacity
+// checks and launch shapes need no device round trip, and enqueues the kernels
+// of one decode step on the caller's stream.
+#include "../../include/pat_decode.h"
+#include "pat_kernels.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace pat;
+
+namespace {
+
+constexpr int64_t kAlign = 256;
+constexpr double kHbmPeak = 8.0e12;
+inline int64_t align_up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+struct Shard {
+    int NL, H, hq, hkv, d, F, Vs, V, qkv_rows, max_pages, n_pages, vocab0;
+};
+
+struct WorkLayout {   // byte offsets inside the work arena
+    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, part_acc, part_ml, logits, next_tok, best_val, rope, report;
+    int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, tmp;
+    int64_t total;
+    int64_t max_chunks;
+};
+
+struct WeightLayout {  // byte offsets inside the weights arena
+    int64_t layer0, layer_stride;
+    int64_t g1, wqkv, wo, g2, wgu, wd;   // within a layer
+    int64_t embed, gf, wlm, total;
+};
+
+int64_t packed_w_bytes(int n, int k) { return (int64_t)cdiv(n, 16) * (k / 32) * 64 * 16; }
+int64_t packed_x_bytes(int b, int k) { return (int64_t)cdiv(b, 16) * (k / 32) * 64 * 16; }
+
+const int kMinChunk = 64;
+
+}  // namespace
+
+struct pat_ctx {
+    pat_cfg cfg;
+    Shard sh;
+    WorkLayout wl;
+    WeightLayout wt;
+    pat_buffers bufs;
+    hipStream_t stream;
+    KvLayout kv;
+    StateArrays st;
+    std::vector<char> layer_loaded;
+    bool final_loaded = false;
+    // host mirror of the live batch
+    int live = 0;
+    std::vector<int32_t> seq_id, kv_len, gen, target, fin;
+    int64_t n_free = 0;
+    int64_t step_index = 0;
+    // pinned staging
+    int32_t *pinned = nullptr;      // 6 * max_batch ints + report
+    // timing
+    bool timing = false;
+    struct Ev { int klass; hipEvent_t a, b; };
+    std::vector<Ev> pending;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
+    double t_ms[3] = {0, 0, 0};
+    int64_t t_n[3] = {0, 0, 0};
+    std::string err;
+};
+
+namespace {
+
+int fail(pat_ctx *c, int code, const char *fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return code;
+}
+
+#define PAT_HIP(ctx, expr)                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(ctx, PAT_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+int derive(const pat_cfg *c, Shard *s, std::string *why)
+{
+    auto bad = [&](const char *m) { if (why) *why = m; return PAT_EINVAL; };
+    if (!c) return bad("cfg is NULL");
+    if (c->n_layers < 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->ffn <= 0 || c->vocab <= 0)
+        return bad("non-positive model dimension");
+    if (c->tp_degree <= 0 || c->tp_rank < 0 || c->tp_rank >= c->tp_degree) return bad("tp_rank outside [0, tp_degree)");
+    if (c->n_q_heads % c->tp_degree || c->ffn % c->tp_degree || c->vocab % c->tp_degree)
+        return bad("heads, ffn and vocab must be divisible by tp_degree");
+    if (c->n_kv_heads % c->tp_degree && c->tp_degree % c->n_kv_heads) return bad("n_kv_heads incompatible with tp_degree");
+    if (c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 64 or 128");
+    if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+    s->NL = c->n_layers; s->H = c->hidden; s->d = c->head_dim; s->V = c->vocab;
+    s->hq = c->n_q_heads / c->tp_degree;
+    s->hkv = std::max(1, c->n_kv_heads / c->tp_degree);
+    s->F = c->ffn / c->tp_degree;
+    s->Vs = c->vocab / c->tp_degree;
+    s->vocab0 = c->tp_rank * s->Vs;
+    s->qkv_rows = (s->hq + 2 * s->hkv) * s->d;
+    const int G = s->hq / s->hkv;
+    if (s->hq % s->hkv || !(G == 1 || G == 2 || G == 4 || G == 8)) return bad("query heads per KV head must be 1, 2, 4 or 8");
+    if (s->H % 32 || (s->hq * s->d) % 32 || s->F % 32) return bad("hidden, hq*head_dim and ffn/tp must be multiples of 32");
+    if (s->Vs % 16) return bad("vocab/tp must be a multiple of 16");
+    if (c->max_batch <= 0 || c->max_batch > 1024) return bad("max_batch must be in [1, 1024]");
+    if (c->page_tokens != 16 && c->page_tokens != 32 && c->page_tokens != 64 && c->page_tokens != 128)
+        return bad("page_tokens must be 16, 32, 64 or 128");
+    if (c->max_seq_len <= 0 || c->kv_token_budget <= 0) return bad("max_seq_len and kv_token_budget must be positive");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 1.f)) return bad("rms_eps must be >= 0 and rope_base > 1");
+    s->max_pages = cdiv(c->max_seq_len, c->page_tokens);
+    const int64_t np = (c->kv_token_budget + c->page_tokens - 1) / c->page_tokens + c->max_batch;
+    if (np > 0x7FFFFFFF) return bad("kv_token_budget too large");
+    s->n_pages = (int)np;
+    return PAT_OK;
+}
+
+void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, int64_t *kv_bytes)
+{
+    const int MB = c->max_batch;
+    int64_t o = 0;
+    auto take = [&](int64_t bytes) { int64_t r = o; o = align_up(o + bytes); return r; };
+    const int kb = std::max(s.hq * s.d, s.F);
+    w->x = take((int64_t)MB * s.H * 4);
+    w->a_hi = take(packed_x_bytes(MB, s.H));
+    w->a_lo = take(packed_x_bytes(MB, s.H));
+    w->b_hi = take(packed_x_bytes(MB, kb));
+    w->b_lo = take(packed_x_bytes(MB, kb));
+    w->qkv = take((int64_t)MB * s.qkv_rows * 4);
+    w->max_chunks = c->kv_token_budget / kMinChunk + 2 * (int64_t)MB;
+    w->part_acc = take(w->max_chunks * s.hq * s.d * 4);
+    w->part_ml = take(w->max_chunks * s.hq * 2 * 4);
+    w->logits = take((int64_t)MB * s.Vs * 4);
+    w->next_tok = take((int64_t)MB * 4);
+    w->best_val = take((int64_t)MB * 4);
+    w->rope = take((int64_t)(c->max_seq_len + 1) * s.d * 4);
+    w->report = take(64);
+    w->seq_id = take(MB * 4); w->tok = take(MB * 4); w->kv_len = take(MB * 4);
+    w->gen = take(MB * 4); w->target = take(MB * 4); w->fin = take(MB * 4);
+    w->page_table = take((int64_t)MB * s.max_pages * 4);
+    w->page_table_tmp = take((int64_t)MB * s.max_pages * 4);
+    w->free_stack = take((int64_t)s.n_pages * 4);
+    w->scalars = take(64);
+    w->chunk_start = take((int64_t)(MB + 1) * 4);
+    w->tmp = take((int64_t)MB * 8 * 4);
+    w->total = o;
+
+    o = 0;
+    wt->g1 = take((int64_t)s.H * 2);
+    wt->g2 = take((int64_t)s.H * 2);
+    wt->wqkv = take(packed_w_bytes(s.qkv_rows, s.H));
+    wt->wo = take(packed_w_bytes(s.H, s.hq * s.d));
+    wt->wgu = take(packed_w_bytes(2 * s.F, s.H));
+    wt->wd = take(packed_w_bytes(s.H, s.F));
+    wt->layer_stride = o;
+    wt->layer0 = 0;
+    o = wt->layer_stride * s.NL;
+    wt->embed = take((int64_t)s.V * s.H * 2);
+    wt->gf = take((int64_t)s.H * 2);
+    wt->wlm = take(packed_w_bytes(s.Vs, s.H));
+    wt->total = o;
+
+    *kv_bytes = align_up((int64_t)s.NL * 2 * s.n_pages * s.hkv * c->page_tokens * s.d * 2);
+}
+
+template <class T> T *at(void *base, int64_t off) { return reinterpret_cast<T *>(static_cast<char *>(base) + off); }
+
+struct TimeScope {   // brackets a launch with events when timing is on
+    pat_ctx *c; int klass; hipEvent_t a = nullptr, b = nullptr;
+    TimeScope(pat_ctx *c_, int k) : c(c_), klass(k)
+    {
+        if (!c->timing) return;
+        if (c->ev_pool.empty()) {
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+        } else { a = c->ev_pool.back().first; b = c->ev_pool.back().second; c->ev_pool.pop_back(); }
+        (void)hipEventRecord(a, c->stream);
+    }
+    ~TimeScope()
+    {
+        if (!a) return;
+        (void)hipEventRecord(b, c->stream);
+        c->pending.push_back({klass, a, b});
+    }
+};
+
+int flush_timing(pat_ctx *c)
+{
+    if (c->pending.empty()) return PAT_OK;
+    PAT_HIP(c, hipStreamSynchronize(c->stream));
+    for (auto &p : c->pending) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) { c->t_ms[p.klass] += ms; c->t_n[p.klass] += 1; }
+        c->ev_pool.emplace_back(p.a, p.b);
+    }
+    c->pending.clear();
+    return PAT_OK;
+}
+
+// Batches beyond 256 rows run as groups of 256 (the weights are streamed once per group).
+hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
+{
+    const int B = g.B;
+    for (int b0 = 0; b0 < B; b0 += 256) {
+        GemmArgs h = g;
+        h.B = std::min(256, B - b0);
+        const int64_t t0 = b0 / 16;
+        h.xhi = g.xhi + t0 * g.KS * 64; h.xlo = g.xlo + t0 * g.KS * 64;
+        if (g.y) h.y = g.y + (int64_t)b0 * g.ldy;
+        if (g.yhi) { h.yhi = g.yhi + t0 * g.KS_out * 64; h.ylo = g.ylo + t0 * g.KS_out * 64; }
+        hipError_t e = launch_gemm(h, mode, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
+{
+    // largest chunk that still gives the chip at least ~2 work items per compute unit
+    int best = kMinChunk;
+    int64_t best_n = 0;
+    for (int C : {256, 128, 64}) {
+        int64_t n = 0;
+        for (int i = 0; i < c->live; ++i) n += (c->kv_len[i] + 1 + C - 1) / C;
+        best = C; best_n = n;
+        if (n * c->sh.hkv >= 512) break;
+    }
+    *n_chunks = best_n;
+    return best;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pat_decode_query(const pat_cfg *cfg, pat_mem_req *out)
+{
+    Shard s;
+    if (!out) return PAT_EINVAL;
+    int rc = derive(cfg, &s, nullptr);
+    if (rc) return rc;
+    WorkLayout w; WeightLayout wt; int64_t kvb;
+    layouts(cfg, s, &w, &wt, &kvb);
+    out->weights_bytes = wt.total; out->kv_bytes = kvb; out->work_bytes = w.total;
+    out->n_pages = s.n_pages; out->max_pages_per_seq = s.max_pages;
+    return PAT_OK;
+}
+
+int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_stream, pat_ctx **out)
+{
+    if (!out || !bufs || !bufs->weights || !bufs->kv || !bufs->work) return PAT_EINVAL;
+    *out = nullptr;
+    Shard s; std::string why;
+    int rc = derive(cfg, &s, &why);
+    if (rc) return rc;
+    if (((uintptr_t)bufs->weights | (uintptr_t)bufs->kv | (uintptr_t)bufs->work) & (kAlign - 1)) return PAT_EINVAL;
+    pat_ctx *c = new pat_ctx();
+    c->cfg = *cfg; c->sh = s; c->bufs = *bufs; c->stream = (hipStream_t)hip_stream;
+    int64_t kvb;
+    layouts(cfg, s, &c->wl, &c->wt, &kvb);
+    c->kv = KvLayout{at<uint16_t>(bufs->kv, 0), s.n_pages, s.hkv, cfg->page_tokens, s.d};
+    void *W = bufs->work;
+    const WorkLayout &w = c->wl;
+    c->st = StateArrays{at<int32_t>(W, w.seq_id), at<int32_t>(W, w.tok), at<int32_t>(W, w.kv_len), at<int32_t>(W, w.gen),
+                        at<int32_t>(W, w.target), at<int32_t>(W, w.fin), at<int32_t>(W, w.page_table),
+                        at<int32_t>(W, w.page_table_tmp), at<int32_t>(W, w.free_stack), at<int32_t>(W, w.scalars),
+                        at<int32_t>(W, w.chunk_start), at<int32_t>(W, w.tmp), s.max_pages, cfg->page_tokens};
+    c->layer_loaded.assign(s.NL, 0);
+    const int MB = cfg->max_batch;
+    c->seq_id.resize(MB); c->kv_len.resize(MB); c->gen.resize(MB); c->target.resize(MB); c->fin.assign(MB, 0);
+    c->n_free = s.n_pages;
+    auto die = [&](const char *what, hipError_t e) { fprintf(stderr, "pat_decode_init: %s: %s\n", what, hipGetErrorString(e)); if (c->pinned) (void)hipHostFree(c->pinned); delete c; return PAT_EHIP; };
+    hipError_t e = hipHostMalloc((void **)&c->pinned, (size_t)(7 * MB + 16) * 4, hipHostMallocDefault);
+    if (e != hipSuccess) { c->pinned = nullptr; return die("hipHostMalloc", e); }
+    // rotary table: cos/sin of pos * base^(-2j/d) evaluated in double, stored as fp32 [pos][d/2][2]
+    {
+        const int half = s.d / 2, npos = cfg->max_seq_len + 1;
+        std::vector<float> cs((size_t)npos * s.d);
+        std::vector<double> inv(half);
+        for (int j = 0; j < half; ++j) inv[j] = std::pow((double)cfg->rope_base, -2.0 * j / (double)s.d);
+        for (int p = 0; p < npos; ++p)
+            for (int j = 0; j < half; ++j) {
+                const double th = (double)p * inv[j];
+                cs[((size_t)p * half + j) * 2] = (float)std::cos(th);
+                cs[((size_t)p * half + j) * 2 + 1] = (float)std::sin(th);
+            }
+        e = hipMemcpyAsync(at<float>(W, w.rope), cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+        if (e != hipSuccess) return die("rotary table upload", e);
+    }
+    e = launch_pool_init(c->st, s.n_pages, c->stream);
+    if (e != hipSuccess) return die("pool init", e);
+    *out = c;
+    return PAT_OK;
+}
+
+int pat_load_layer(pat_ctx *c, int32_t layer, const pat_layer_weights *w)
+{
+    if (!c) return PAT_EINVAL;
+    if (!w || layer < 0 || layer >= c->sh.NL) return fail(c, PAT_EINVAL, "layer %d outside [0, %d)", layer, c->sh.NL);
+    if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(c, PAT_EINVAL, "NULL weight pointer");
+    const Shard &s = c->sh;
+    char *L = at<char>(c->bufs.weights, c->wt.layer0 + c->wt.layer_stride * layer);
+    PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wqkv, nullptr, s.qkv_rows, s.H, (uint4 *)(L + c->wt.wqkv), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wo, nullptr, s.H, s.hq * s.d, (uint4 *)(L + c->wt.wo), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wg, (const uint16_t *)w->wu, s.F, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wd, nullptr, s.H, s.F, (uint4 *)(L + c->wt.wd), c->stream));
+    c->layer_loaded[layer] = 1;
+    return PAT_OK;
+}
+
+int pat_load_final(pat_ctx *c, const pat_final_weights *w)
+{
+    if (!c) return PAT_EINVAL;
+    if (!w || !w->embed || !w->gf || !w->wlm) return fail(c, PAT_EINVAL, "NULL weight pointer");
+    const Shard &s = c->sh;
+    char *Wb = at<char>(c->bufs.weights, 0);
+    PAT_HIP(c, hipMemcpyAsync(Wb + c->wt.embed, w->embed, (size_t)s.V * s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    PAT_HIP(c, hipMemcpyAsync(Wb + c->wt.gf, w->gf, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wlm, nullptr, s.Vs, s.H, (uint4 *)(Wb + c->wt.wlm), c->stream));
+    c->final_loaded = true;
+    return PAT_OK;
+}
+
+int pat_decode_admit(pat_ctx *c, int32_t n, const int32_t *seq_id, const int32_t *token, const int32_t *kv_len,
+                     const int32_t *target_len)
+{
+    if (!c) return PAT_EINVAL;
+    if (n <= 0 || !seq_id || !token || !kv_len || !target_len) return fail(c, PAT_EINVAL, "admit: bad arguments");
+    const int MB = c->cfg.max_batch, P = c->cfg.page_tokens;
+    if (c->live + n > MB) return fail(c, PAT_ENOMEM, "admit: %d + %d sequences exceed max_batch %d", c->live, n, MB);
+    int64_t pages = 0;
+    for (int i = 0; i < n; ++i) {
+        if (kv_len[i] < 0 || target_len[i] < 1) return fail(c, PAT_EINVAL, "admit: kv_len < 0 or target < 1 at %d", i);
+        if ((int64_t)kv_len[i] + target_len[i] > c->cfg.max_seq_len)
+            return fail(c, PAT_EINVAL, "admit: sequence %d would reach %lld tokens > max_seq_len %d", i,
+                        (long long)kv_len[i] + target_len[i], c->cfg.max_seq_len);
+        if (token[i] < 0 || token[i] >= c->sh.V) return fail(c, PAT_EINVAL, "admit: token id %d outside the vocabulary", token[i]);
+        pages += cdiv(kv_len[i], P);
+    }
+    if (pages > c->n_free) return fail(c, PAT_ENOMEM, "admit: %lld pages needed, %lld free", (long long)pages, (long long)c->n_free);
+    for (int k = 0; k < c->live; ++k) if (c->fin[k]) return fail(c, PAT_ESTATE, "admit: compact finished slots first");
+    // stage [seq_id | tok | kv_len | gen | target | fin] for the new slots
+    int32_t *p = c->pinned;
+    for (int i = 0; i < n; ++i) {
+        p[0 * MB + i] = seq_id[i]; p[1 * MB + i] = token[i]; p[2 * MB + i] = kv_len[i];
+        p[3 * MB + i] = 0; p[4 * MB + i] = target_len[i]; p[5 * MB + i] = 0;
+    }
+    int32_t *dst[6] = {c->st.seq_id, c->st.tok, c->st.kv_len, c->st.gen, c->st.target, c->st.fin};
+    for (int a = 0; a < 6; ++a)
+        PAT_HIP(c, hipMemcpyAsync(dst[a] + c->live, p + a * MB, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    PAT_HIP(c, launch_admit(c->st, c->live, n, c->stream));
+    PAT_HIP(c, hipStreamSynchronize(c->stream));   // the staging buffer is reused by the next call
+    for (int i = 0; i < n; ++i) {
+        const int k = c->live + i;
+        c->seq_id[k] = seq_id[i]; c->kv_len[k] = kv_len[i]; c->gen[k] = 0; c->target[k] = target_len[i]; c->fin[k] = 0;
+    }
+    c->live += n;
+    c->n_free -= pages;
+    return PAT_OK;
+}
+
+static int kv_copy(pat_ctx *c, int32_t slot, int32_t layer, void *k, void *v, int32_t n_tokens, int to_pool)
+{
+    if (!c) return PAT_EINVAL;
+    if (slot < 0 || slot >= c->live || layer < 0 || layer >= c->sh.NL || !k || !v)
+        return fail(c, PAT_EINVAL, "kv copy: slot %d / layer %d out of range or NULL buffer", slot, layer);
+    if (n_tokens < 0 || n_tokens > c->kv_len[slot]) return fail(c, PAT_EINVAL, "kv copy: %d tokens, slot holds %d", n_tokens, c->kv_len[slot]);
+    PAT_HIP(c, launch_kv_copy(c->kv, layer, c->st.page_table + (int64_t)slot * c->sh.max_pages, (uint16_t *)k, (uint16_t *)v,
+                              n_tokens, to_pool, c->stream));
+    return PAT_OK;
+}
+
+int pat_kv_write(pat_ctx *c, int32_t slot, int32_t layer, const void *k, const void *v, int32_t n)
+{
+    return kv_copy(c, slot, layer, const_cast<void *>(k), const_cast<void *>(v), n, 1);
+}
+
+int pat_kv_read(pat_ctx *c, int32_t slot, int32_t layer, void *k, void *v, int32_t n) { return kv_copy(c, slot, layer, k, v, n, 0); }
+
+int pat_step_algo_bytes(pat_ctx *c, double *weight_bytes, double *kv_bytes)
+{
+    if (!c) return PAT_EINVAL;
+    const Shard &s = c->sh;
+    const double per_layer = 2.0 * ((double)s.H * s.qkv_rows + (double)s.hq * s.d * s.H + 3.0 * s.H * s.F);
+    double ctx = 0;
+    for (int i = 0; i < c->live; ++i) ctx += c->kv_len[i] + 1;
+    if (weight_bytes) *weight_bytes = s.NL * per_layer + 2.0 * s.Vs * s.H;
+    if (kv_bytes) *kv_bytes = (double)s.NL * 2 * s.hkv * s.d * 2 * (ctx + c->live);
+    return PAT_OK;
+}
+
+int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_dev, float *logits_dev)
+{
+    if (!c) return PAT_EINVAL;
+    const Shard &s = c->sh;
+    const int B = c->live;
+    if (B <= 0) return fail(c, PAT_ESTATE, "step: the live batch is empty");
+    if (!c->final_loaded) return fail(c, PAT_ESTATE, "step: final weights not loaded");
+    for (int l = 0; l < s.NL; ++l) if (!c->layer_loaded[l]) return fail(c, PAT_ESTATE, "step: layer %d not loaded", l);
+    const int P = c->cfg.page_tokens;
+    int64_t new_pages = 0;
+    for (int i = 0; i < B; ++i) {
+        if (c->fin[i]) return fail(c, PAT_ESTATE, "step: slot %d is finished; call pat_kv_compact first", i);
+        if (c->kv_len[i] + 1 > c->cfg.max_seq_len) return fail(c, PAT_EINVAL, "step: slot %d exceeds max_seq_len", i);
+        new_pages += (c->kv_len[i] % P) == 0;
+    }
+    if (new_pages > c->n_free) return fail(c, PAT_ENOMEM, "step: %lld new pages needed, %lld free", (long long)new_pages, (long long)c->n_free);
+    int64_t n_chunks = 0;
+    const int C = pick_chunk(c, &n_chunks);
+    if (n_chunks > c->wl.max_chunks) return fail(c, PAT_ENOMEM, "step: %lld attention chunks exceed the workspace (%lld)", (long long)n_chunks, (long long)c->wl.max_chunks);
+
+    void *W = c->bufs.work;
+    const WorkLayout &w = c->wl;
+    hipStream_t st = c->stream;
+    float *x = at<float>(W, w.x), *qkv = at<float>(W, w.qkv);
+    uint4 *a_hi = at<uint4>(W, w.a_hi), *a_lo = at<uint4>(W, w.a_lo), *b_hi = at<uint4>(W, w.b_hi), *b_lo = at<uint4>(W, w.b_lo);
+    float *logits = logits_dev ? logits_dev : at<float>(W, w.logits);
+    int32_t *next_tok = next_tok_dev ? next_tok_dev : at<int32_t>(W, w.next_tok);
+    char *Wb = at<char>(c->bufs.weights, 0);
+
+    { TimeScope t(c, 2); PAT_HIP(c, launch_plan_step(c->st, B, C, st)); }
+    { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
+
+    AttnArgs aa{};
+    aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = c->st.kv_len;
+    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_tokens = C;
+    aa.part_acc = at<float>(W, w.part_acc); aa.part_ml = at<float>(W, w.part_ml); aa.ohi = b_hi; aa.olo = b_lo;
+    aa.n_items = (int)(n_chunks * s.hkv);
+
+    for (int l = 0; l < s.NL; ++l) {
+        char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        {
+            GemmArgs g{(const uint4 *)(L + c->wt.wqkv), s.qkv_rows / 16, s.H / 32, a_hi, a_lo, B, qkv, s.qkv_rows, s.qkv_rows, nullptr, nullptr, 0};
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
+        }
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st, at<float>(W, w.rope), B, st)); }
+        aa.layer = l;
+        { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
+        {
+            GemmArgs g{(const uint4 *)(L + c->wt.wo), s.H / 16, s.hq * s.d / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0};
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
+        }
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        {
+            GemmArgs g{(const uint4 *)(L + c->wt.wgu), 2 * s.F / 16, s.H / 32, a_hi, a_lo, B, nullptr, 0, 2 * s.F, b_hi, b_lo, s.F / 32};
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
+        }
+        {
+            GemmArgs g{(const uint4 *)(L + c->wt.wd), s.H / 16, s.F / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0};
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
+        }
+    }
+    { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+    {
+        GemmArgs g{(const uint4 *)(Wb + c->wt.wlm), s.Vs / 16, s.H / 32, a_hi, a_lo, B, logits, s.Vs, s.Vs, nullptr, nullptr, 0};
+        TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
+    }
+    { TimeScope t(c, 2); PAT_HIP(c, launch_argmax(logits, B, s.Vs, s.vocab0, next_tok, at<float>(W, w.best_val), st)); }
+    { TimeScope t(c, 2); PAT_HIP(c, launch_finish(c->st, next_tok, B, c->cfg.eos_token, at<char>(W, w.report), st)); }
+
+    // host mirror
+    c->n_free -= new_pages;
+    c->step_index += 1;
+    int n_fin = 0; int64_t sum_ctx = 0;
+    for (int i = 0; i < B; ++i) {
+        c->kv_len[i] += 1; c->gen[i] += 1;
+        c->fin[i] = c->gen[i] >= c->target[i];
+        n_fin += c->fin[i]; sum_ctx += c->kv_len[i];
+    }
+    const bool need_flags = c->cfg.eos_token >= 0;
+    if (report_host || need_flags) {
+        int32_t *rep = c->pinned + 6 * c->cfg.max_batch;
+        PAT_HIP(c, hipMemcpyAsync(rep, at<char>(W, w.report), sizeof(pat_step_report), hipMemcpyDeviceToHost, st));
+        if (need_flags) PAT_HIP(c, hipMemcpyAsync(c->pinned, c->st.fin, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+        PAT_HIP(c, hipStreamSynchronize(st));
+        if (need_flags) for (int i = 0; i < B; ++i) c->fin[i] = c->pinned[i];
+        if (report_host) {
+            memcpy(report_host, rep, sizeof(pat_step_report));
+            if (!need_flags && (report_host->n_finished != n_fin || report_host->sum_context != sum_ctx || report_host->free_pages != c->n_free))
+                return fail(c, PAT_ESTATE, "step: device state (fin %d, ctx %lld, free %d) disagrees with the host mirror (%d, %lld, %lld)",
+                            report_host->n_finished, (long long)report_host->sum_context, report_host->free_pages, n_fin,
+                            (long long)sum_ctx, (long long)c->n_free);
+        }
+    }
+    return PAT_OK;
+}
+
+int pat_kv_compact(pat_ctx *c, int32_t *new_live_host)
+{
+    if (!c) return PAT_EINVAL;
+    const int B = c->live, P = c->cfg.page_tokens;
+    int nf = 0;
+    for (int i = 0; i < B; ++i) nf += c->fin[i] != 0;
+    if (nf > 0) {
+        { TimeScope t(c, 2); PAT_HIP(c, launch_compact(c->st, B, c->stream)); }
+        int k = 0;
+        for (int j = 0; j < B; ++j) {
+            if (c->fin[j]) { c->n_free += cdiv(c->kv_len[j], P); continue; }
+            c->seq_id[k] = c->seq_id[j]; c->kv_len[k] = c->kv_len[j]; c->gen[k] = c->gen[j]; c->target[k] = c->target[j];
+            ++k;
+        }
+        for (int j = 0; j < B; ++j) c->fin[j] = 0;
+        c->live = k;
+    }
+    if (new_live_host) *new_live_host = c->live;
+    return PAT_OK;
+}
+
+int pat_get_state(pat_ctx *c, int32_t *live, int32_t *seq_id, int32_t *token, int32_t *kv_len, int32_t *gen,
+                  int32_t *target, int32_t *fin)
+{
+    if (!c) return PAT_EINVAL;
+    const int B = c->live, MB = c->cfg.max_batch;
+    int32_t *src[6] = {c->st.seq_id, c->st.tok, c->st.kv_len, c->st.gen, c->st.target, c->st.fin};
+    int32_t *dst[6] = {seq_id, token, kv_len, gen, target, fin};
+    if (B > 0)
+        for (int a = 0; a < 6; ++a)
+            PAT_HIP(c, hipMemcpyAsync(c->pinned + a * MB, src[a], (size_t)B * 4, hipMemcpyDeviceToHost, c->stream));
+    int32_t *sc = c->pinned + 6 * MB;
+    PAT_HIP(c, hipMemcpyAsync(sc, c->st.scalars, 32, hipMemcpyDeviceToHost, c->stream));
+    PAT_HIP(c, hipStreamSynchronize(c->stream));
+    if (sc[7] != 0) return fail(c, PAT_ESTATE, "device page allocator reported error %d", sc[7]);
+    if (sc[1] != B) return fail(c, PAT_ESTATE, "device live batch %d != host mirror %d", sc[1], B);
+    if (live) *live = B;
+    for (int a = 0; a < 6; ++a) if (dst[a] && B > 0) memcpy(dst[a], c->pinned + a * MB, (size_t)B * 4);
+    return PAT_OK;
+}
+
+int pat_get_pages(pat_ctx *c, int32_t *page_table_host, int32_t *free_list_host, int32_t *n_free)
+{
+    if (!c) return PAT_EINVAL;
+    PAT_HIP(c, hipStreamSynchronize(c->stream));
+    int32_t sc[8];
+    PAT_HIP(c, hipMemcpy(sc, c->st.scalars, 32, hipMemcpyDeviceToHost));
+    if (page_table_host && c->live > 0)
+        PAT_HIP(c, hipMemcpy(page_table_host, c->st.page_table, (size_t)c->live * c->sh.max_pages * 4, hipMemcpyDeviceToHost));
+    if (free_list_host && sc[0] > 0) PAT_HIP(c, hipMemcpy(free_list_host, c->st.free_stack, (size_t)sc[0] * 4, hipMemcpyDeviceToHost));
+    if (n_free) *n_free = sc[0];
+    if (sc[0] != c->n_free) return fail(c, PAT_ESTATE, "device free pages %d != host mirror %lld", sc[0], (long long)c->n_free);
+    return PAT_OK;
+}
+
+int pat_decode_reset(pat_ctx *c)
+{
+    if (!c) return PAT_EINVAL;
+    PAT_HIP(c, launch_pool_init(c->st, c->sh.n_pages, c->stream));
+    c->live = 0; c->n_free = c->sh.n_pages;
+    std::fill(c->fin.begin(), c->fin.end(), 0);
+    return PAT_OK;
+}
+
+int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32_t *kv_lens, int32_t nl, int64_t t_cap,
+                     int32_t steps, int32_t warmup, int32_t reps, uint64_t seed, pat_grid_row *rows, int32_t *n_rows)
+{
+    if (!c) return PAT_EINVAL;
+    if (!batches || !kv_lens || !rows || !n_rows || nb <= 0 || nl <= 0 || steps <= 0 || warmup < 0 || reps <= 0)
+        return fail(c, PAT_EINVAL, "profile_grid: bad arguments");
+    if (*n_rows < nb * nl) return fail(c, PAT_EINVAL, "profile_grid: rows_out holds %d rows, %d needed", *n_rows, nb * nl);
+    const Shard &s = c->sh;
+    const int P = c->cfg.page_tokens;
+    PAT_HIP(c, launch_kv_fill(c->kv, s.NL, seed, c->stream));
+    hipEvent_t e0, e1;
+    PAT_HIP(c, hipEventCreate(&e0));
+    PAT_HIP(c, hipEventCreate(&e1));
+    std::vector<int32_t> ids, toks, lens, tgts;
+    int r = 0;
+    int rc = PAT_OK;
+    for (int ib = 0; ib < nb && rc == PAT_OK; ++ib)
+        for (int il = 0; il < nl && rc == PAT_OK; ++il, ++r) {
+            pat_grid_row &row = rows[r];
+            memset(&row, 0, sizeof row);
+            const int B = batches[ib], L = kv_lens[il];
+            row.tp_degree = c->cfg.tp_degree; row.batch = B; row.kv_len = L;
+            const int total_steps = warmup + steps;
+            if (B <= 0 || L < 0) { rc = fail(c, PAT_EINVAL, "profile_grid: batch %d / kv_len %d", B, L); break; }
+            if ((int64_t)B * L > t_cap) { row.skipped = 1; continue; }
+            const int64_t pages = (int64_t)B * cdiv(L + total_steps, P);
+            if (B > c->cfg.max_batch || L + total_steps > c->cfg.max_seq_len || pages > s.n_pages ||
+                (int64_t)B * (cdiv(L + total_steps, kMinChunk) + 1) > c->wl.max_chunks) { row.skipped = 2; continue; }
+            ids.resize(B); toks.resize(B); lens.assign(B, L); tgts.assign(B, total_steps + 1);
+            double sum = 0, sum2 = 0, mn = 1e300;
+            for (int rep = 0; rep < reps && rc == PAT_OK; ++rep) {
+                if ((rc = pat_decode_reset(c)) != PAT_OK) break;
+                for (int i = 0; i < B; ++i) { ids[i] = i; toks[i] = (int32_t)((seed + 7919u * i + 104729u * rep) % (uint64_t)s.V); }
+                if ((rc = pat_decode_admit(c, B, ids.data(), toks.data(), lens.data(), tgts.data())) != PAT_OK) break;
+                for (int w = 0; w < warmup && rc == PAT_OK; ++w) rc = pat_decode_step(c, nullptr, nullptr, nullptr);
+                if (rc != PAT_OK) break;
+                if (rep == 0) {
+                    row.sum_context = (int64_t)B * (L + warmup);
+                    // algorithmic bytes at the middle of the timed window
+                    double wb, kb; pat_step_algo_bytes(c, &wb, &kb);
+                    const double kv_mid = (double)s.NL * 2 * s.hkv * s.d * 2 * ((double)B * (L + warmup + steps / 2 + 1) + B);
+                    row.algo_bytes = wb + kv_mid;
+                }
+                if (hipEventRecord(e0, c->stream) != hipSuccess) { rc = fail(c, PAT_EHIP, "event record"); break; }
+                for (int t = 0; t < steps && rc == PAT_OK; ++t) rc = pat_decode_step(c, nullptr, nullptr, nullptr);
+                if (rc != PAT_OK) break;
+                if (hipEventRecord(e1, c->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { rc = fail(c, PAT_EHIP, "event sync"); break; }
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, e0, e1);
+                const double us = 1e3 * ms / steps;
+                sum += us; sum2 += us * us; mn = std::min(mn, us);
+            }
+            if (rc != PAT_OK) break;
+            row.mean_us = sum / reps; row.min_us = mn;
+            row.std_us = std::sqrt(std::max(0.0, sum2 / reps - row.mean_us * row.mean_us));
+            row.tokens_per_s = B / (row.mean_us * 1e-6);
+            row.hbm_frac = row.algo_bytes / (row.mean_us * 1e-6) / kHbmPeak;
+        }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (rc == PAT_OK) { *n_rows = nb * nl; rc = pat_decode_reset(c); }
+    return rc;
+}
+
+int pat_timing_enable(pat_ctx *c, int32_t on)
+{
+    if (!c) return PAT_EINVAL;
+    int rc = flush_timing(c);
+    c->timing = on != 0;
+    return rc;
+}
+
+int pat_timing_read(pat_ctx *c, int32_t klass, double *total_ms, int64_t *launches, int32_t reset)
+{
+    if (!c || klass < 0 || klass > 2) return PAT_EINVAL;
+    int rc = flush_timing(c);
+    if (rc) return rc;
+    if (total_ms) *total_ms = c->t_ms[klass];
+    if (launches) *launches = c->t_n[klass];
+    if (reset) { c->t_ms[klass] = 0; c->t_n[klass] = 0; }
+    return PAT_OK;
+}
+
+int pat_decode_destroy(pat_ctx *c)
+{
+    if (!c) return PAT_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    for (auto &p : c->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    for (auto &p : c->ev_pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    delete c;
+    return PAT_OK;
+}
+
+const char *pat_last_error(const pat_ctx *c) { return c ? c->err.c_str() : "NULL context"; }
+
+// ---- single operators -------------------------------------------------------------
+
+int64_t pat_op_packed_weight_bytes(int32_t n, int32_t k) { return (n <= 0 || k <= 0 || k % 32) ? -1 : packed_w_bytes(n, k); }
+int64_t pat_op_packed_act_bytes(int32_t b, int32_t k) { return (b <= 0 || k <= 0 || k % 32) ? -1 : packed_x_bytes(b, k); }
+
+int pat_op_pack_weight(const void *w, const void *w2, int32_t n, int32_t k, void *packed, void *stream)
+{
+    if (!w || !packed || n <= 0 || k <= 0 || k % 32) return PAT_EINVAL;
+    return launch_pack_weight((const uint16_t *)w, (const uint16_t *)w2, n, k, (uint4 *)packed, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, void *stream)
+{
+    if (!x || !xhi || !xlo || b <= 0 || k <= 0 || k % 32) return PAT_EINVAL;
+    return launch_pack_act(x, b, k, (uint4 *)xhi, (uint4 *)xlo, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b, float *y,
+                int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *stream)
+{
+    if (!w_packed || !xhi || !xlo || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256 || mode < 0 || mode > 2) return PAT_EINVAL;
+    if (mode == kGemmSwiGLU) { if (!y_hi || !y_lo || n % 2 || (n / 2) % 32) return PAT_EINVAL; }
+    else if (!y || ldy < n) return PAT_EINVAL;
+    GemmArgs g{(const uint4 *)w_packed, cdiv(n, 16), k / 32, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, n,
+               (uint4 *)y_hi, (uint4 *)y_lo, mode == kGemmSwiGLU ? n / 2 / 32 : 0};
+    return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo, void *stream)
+{
+    if (!x || !g || !xhi || !xlo || b <= 0 || h <= 0 || h % 32) return PAT_EINVAL;
+    return launch_rmsnorm_pack(x, (const uint16_t *)g, b, h, eps, (uint4 *)xhi, (uint4 *)xlo, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val, void *stream)
+{
+    if (!logits || !out_idx || b <= 0 || n <= 0) return PAT_EINVAL;
+    return launch_argmax(logits, b, n, base, out_idx, out_val, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+}  // extern "C"

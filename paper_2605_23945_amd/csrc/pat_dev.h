@@ -1,0 +1,62 @@
+// Device-side helpers shared by the HIP kernels of the decode step (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pat {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round-to-nearest-even; finite inputs and infinities (NaN is mapped to a quiet NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// the two bf16 values held in one 32-bit word, widened
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// x = hi + lo + O(2^-17 |x|), both bf16: the operand split that keeps fp32-class
+// accuracy on the bf16 matrix cores.
+__device__ __forceinline__ void split_bf16(float v, uint16_t &hi, uint16_t &lo)
+{
+    hi = f32_to_bf16(v);
+    lo = f32_to_bf16(v - bf16_to_f32(hi));
+}
+
+// Packed operand layouts for v_mfma_f32_16x16x32_bf16.  A k-step is 32
+// consecutive k; lane l of a wave holds 8 consecutive k (group g = l / 16) of
+// row r = l % 16, i.e. one 16-byte vector; a (16-row tile, k-step) block is the
+// 64 lanes' vectors back to back = 1 KiB.
+//   vector index of (tile, kstep, lane) = (tile * KS + kstep) * 64 + lane
+// Offset in bf16 elements of element (row, k) of a [rows, K] operand:
+__device__ __host__ __forceinline__ int64_t packed_elem_offset(int row, int k, int KS)
+{
+    int tile = row >> 4, r = row & 15, ks = k >> 5, g = (k & 31) >> 3, j = k & 7;
+    return ((((int64_t)tile * KS + ks) * 64 + g * 16 + r) << 3) + j;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+}  // namespace pat

@@ -1,0 +1,79 @@
+// Host-side launchers of the HIP kernels (internal to libpat_decode.so).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pat {
+
+// ---- weight-streaming projections (gemm_stream.hip) ---------------------------
+enum GemmMode { kGemmStore = 0, kGemmAccum = 1, kGemmSwiGLU = 2 };
+
+struct GemmArgs {
+    const uint4 *w;            // packed weights: [n_tiles][KS][64] vectors
+    int n_tiles, KS;           // 16-row tiles, 32-wide k-steps
+    const uint4 *xhi, *xlo;    // packed split-bf16 activations: [b_tiles][KS][64]
+    int B;                     // live rows
+    float *y;                  // [B, ldy] fp32 (store / accumulate)
+    int ldy, n_valid;          // row stride of y, number of real output columns
+    uint4 *yhi, *ylo;          // SwiGLU: packed split-bf16 output [b_tiles][KS_out][64]
+    int KS_out;
+};
+
+hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s);
+hipError_t launch_pack_act(const float *x, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);
+hipError_t launch_rmsnorm_pack(const float *x, const uint16_t *g, int b, int h, float eps, uint4 *hi, uint4 *lo,
+                               hipStream_t s);
+hipError_t launch_gemm(const GemmArgs &a, int mode, hipStream_t s);
+
+// ---- attention over the paged cache (attention.hip) ----------------------------
+struct KvLayout {
+    uint16_t *pool;            // [layer][2][n_pages][hkv][P][d] bf16
+    int n_pages, hkv, P, d;
+    __host__ __device__ int64_t page_elems() const { return (int64_t)hkv * P * d; }
+    __host__ __device__ int64_t base(int layer, int kv) const { return ((int64_t)layer * 2 + kv) * n_pages * page_elems(); }
+};
+
+struct AttnArgs {
+    KvLayout kv;
+    int layer;
+    const float *qkv;          // [B, ldq]: rotated q heads first
+    int ldq, hq, B;
+    const int32_t *kv_len;     // tokens cached BEFORE this step (the new one sits at index kv_len)
+    const int32_t *page_table; // [max_batch][max_pages]
+    int max_pages;
+    const int32_t *chunk_start;// [B + 1] exclusive prefix of per-slot chunk counts
+    int chunk_tokens;
+    float *part_acc;           // [n_chunks_total][hq][d]
+    float *part_ml;            // [n_chunks_total][hq][2]  (max, sum)
+    uint4 *ohi, *olo;          // merged output as packed split-bf16 [B, hq*d]
+    int n_items;               // n_chunks_total * hkv (host mirror)
+};
+hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s);
+
+// ---- small kernels (step_misc.hip) ----------------------------------------------
+struct StateArrays {           // device int32 arrays of max_batch entries
+    int32_t *seq_id, *tok, *kv_len, *gen, *target, *fin;
+    int32_t *page_table;       // [max_batch][max_pages]
+    int32_t *page_table_tmp;
+    int32_t *free_stack;       // [n_pages]
+    int32_t *scalars;          // [0] n_free, [1] live, [2] n_finished, [3] chunks_total, [4..5] sum_ctx (int64), [6] step, [7] error
+    int32_t *chunk_start;      // [max_batch + 1]
+    int32_t *tmp;              // [8 * max_batch] scratch for compaction
+    int max_pages, P;
+};
+
+hipError_t launch_pool_init(const StateArrays &st, int n_pages, hipStream_t s);
+hipError_t launch_admit(const StateArrays &st, int live, int n, hipStream_t s);   // new slots' arrays already copied in
+hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipStream_t s);
+hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s);
+hipError_t launch_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const StateArrays &st,
+                              const float *rope_cs, int B, hipStream_t s);
+hipError_t launch_argmax(const float *logits, int B, int n, int base, int32_t *out_idx, float *out_val, hipStream_t s);
+hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, int eos, void *report_dev, hipStream_t s);
+hipError_t launch_compact(const StateArrays &st, int B, hipStream_t s);
+hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, uint16_t *k, uint16_t *v, int n_tokens,
+                          int to_pool, hipStream_t s);
+hipError_t launch_kv_fill(const KvLayout &kv, int n_layers, uint64_t seed, hipStream_t s);
+
+}  // namespace pat

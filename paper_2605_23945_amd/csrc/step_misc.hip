@@ -1,0 +1,350 @@
+// The small kernels of the decode step: page pool and live-batch bookkeeping
+// (admit, per-step plan, finish flags, stable compaction), embedding gather,
+// rotary embedding + KV append, greedy argmax, and page <-> contiguous K/V copies.
+// All integer bookkeeping runs in single-workgroup kernels with fixed-order block
+// scans, so page assignment and compaction are deterministic.
+#include "pat_dev.h"
+#include "pat_kernels.h"
+
+namespace pat {
+
+namespace {
+
+constexpr int kBlk = 1024;   // = the largest live batch
+
+enum { S_NFREE = 0, S_LIVE = 1, S_NFIN = 2, S_CHUNKS = 3, S_SUMCTX = 4 /* int64 in [4],[5] */, S_STEP = 6, S_ERR = 7 };
+
+// Exclusive prefix sum over the workgroup's 1024 threads (thread order), total returned to all.
+__device__ int block_exclusive_scan(int v, int &total)
+{
+    __shared__ int wsum[kBlk / 64];
+    __shared__ int wtot;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();              // protects wsum/wtot against the previous call's readers
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < kBlk / 64; ++w) { const int t = wsum[w]; wsum[w] = run; run += t; }
+        wtot = run;
+    }
+    __syncthreads();
+    total = wtot;
+    return wsum[wave] + inc - v;
+}
+
+__global__ void pool_init_kernel(StateArrays st, int n_pages)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_pages) st.free_stack[i] = n_pages - 1 - i;   // page 0 is popped first
+    if (i < 8) st.scalars[i] = (i == S_NFREE) ? n_pages : 0;
+}
+
+// Slots [live, live + n) were filled by the host; give each ceil(kv_len / P) pages.
+__global__ __launch_bounds__(kBlk) void admit_kernel(StateArrays st, int live, int n)
+{
+    const int i = threadIdx.x;
+    const int slot = live + i;
+    const int need = (i < n) ? (st.kv_len[slot] + st.P - 1) / st.P : 0;
+    int total;
+    const int off = block_exclusive_scan(need, total);
+    const int n_free = st.scalars[S_NFREE];
+    if (total > n_free) { if (i == 0) st.scalars[S_ERR] = 1; return; }
+    for (int p = 0; p < need; ++p) st.page_table[(int64_t)slot * st.max_pages + p] = st.free_stack[n_free - 1 - (off + p)];
+    __syncthreads();
+    if (i == 0) { st.scalars[S_NFREE] = n_free - total; st.scalars[S_LIVE] = live + n; }
+}
+
+// Before a step: per-slot chunk counts -> exclusive prefix; a fresh page for
+// every slot whose next token starts a new page.
+__global__ __launch_bounds__(kBlk) void plan_step_kernel(StateArrays st, int B, int C)
+{
+    const int i = threadIdx.x;
+    const int L = (i < B) ? st.kv_len[i] : 0;
+    const int chunks = (i < B) ? (L + 1 + C - 1) / C : 0;
+    const int need = (i < B && (L % st.P) == 0) ? 1 : 0;
+    int tot_c, tot_p;
+    const int off_c = block_exclusive_scan(chunks, tot_c);
+    const int off_p = block_exclusive_scan(need, tot_p);
+    if (i < B) st.chunk_start[i] = off_c;
+    if (i == 0) { st.chunk_start[B] = tot_c; st.scalars[S_CHUNKS] = tot_c; }
+    const int n_free = st.scalars[S_NFREE];
+    if (tot_p > n_free) { if (i == 0) st.scalars[S_ERR] = 2; return; }
+    if (need) st.page_table[(int64_t)i * st.max_pages + L / st.P] = st.free_stack[n_free - 1 - off_p];
+    __syncthreads();
+    if (i == 0) st.scalars[S_NFREE] = n_free - tot_p;
+}
+
+__global__ void embed_kernel(const uint16_t *table, int H, const int32_t *tok, float *x)
+{
+    const int b = blockIdx.x;
+    const uint16_t *row = table + (int64_t)tok[b] * H;
+    for (int k0 = threadIdx.x * 8; k0 < H; k0 += blockDim.x * 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(row + k0);
+        float *o = x + (int64_t)b * H + k0;
+        *reinterpret_cast<float4 *>(o) = make_float4(bf16lo(v.x), bf16hi(v.x), bf16lo(v.y), bf16hi(v.y));
+        *reinterpret_cast<float4 *>(o + 4) = make_float4(bf16lo(v.z), bf16hi(v.z), bf16lo(v.w), bf16hi(v.w));
+    }
+}
+
+// One workgroup per sequence.  Position = tokens already cached.  q heads are
+// rotated in place (fp32); the new k (rotated) and v are rounded to bf16
+// (nearest-even) and written into the slot's page.
+__global__ __launch_bounds__(256) void rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
+                                                          StateArrays st, const float *rope_cs)
+{
+    const int b = blockIdx.x;
+    const int D = kv.d, half = D / 2, hkv = kv.hkv, P = kv.P;
+    const int pos = st.kv_len[b];
+    const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
+    float *row = qkv + (int64_t)b * ldq;
+    const float *cs = rope_cs + (int64_t)pos * D;   // [half][2]
+    uint16_t *kdst = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + (int64_t)(pos % P) * D;
+    uint16_t *vdst = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + (int64_t)(pos % P) * D;
+    const int n_pairs = (hq + hkv) * half;
+    for (int i = threadIdx.x; i < n_pairs; i += blockDim.x) {
+        const int head = i / half, j = i - head * half;
+        const float c = cs[2 * j], s = cs[2 * j + 1];
+        float *p = row + head * D;
+        const float x0 = p[j], x1 = p[j + half];
+        const float r0 = x0 * c - x1 * s, r1 = x0 * s + x1 * c;
+        if (head < hq) {
+            p[j] = r0; p[j + half] = r1;
+        } else {
+            uint16_t *d = kdst + (int64_t)(head - hq) * P * D;
+            d[j] = f32_to_bf16(r0); d[j + half] = f32_to_bf16(r1);
+        }
+    }
+    const float *vsrc = row + (hq + hkv) * D;
+    for (int i = threadIdx.x; i < hkv * D; i += blockDim.x) {
+        const int head = i / D, e = i - head * D;
+        vdst[(int64_t)head * P * D + e] = f32_to_bf16(vsrc[i]);
+    }
+}
+
+// (max, lowest index) of one row per workgroup; NaN never wins.
+__global__ __launch_bounds__(kBlk) void argmax_kernel(const float *logits, int n, int base, int32_t *out_idx,
+                                                      float *out_val)
+{
+    __shared__ float sv[kBlk / 64];
+    __shared__ int si[kBlk / 64];
+    const float *row = logits + (int64_t)blockIdx.x * n;
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int i = threadIdx.x; i < n; i += kBlk) {
+        const float a = row[i];
+        if (a > bv) { bv = a; bi = i; }      // false for NaN; increasing i keeps the first maximum
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlk / 64; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        if (bi == 0x7FFFFFFF) bi = 0;
+        out_idx[blockIdx.x] = base + bi;
+        if (out_val) out_val[blockIdx.x] = bv;
+    }
+}
+
+struct ReportDev { int32_t live, n_fin; int64_t sum_ctx; int32_t n_free, step; };
+
+__global__ __launch_bounds__(kBlk) void finish_kernel(StateArrays st, const int32_t *next_tok, int B, int eos,
+                                                      ReportDev *rep)
+{
+    __shared__ int s_fin;
+    __shared__ unsigned long long s_ctx;
+    if (threadIdx.x == 0) { s_fin = 0; s_ctx = 0; }
+    __syncthreads();
+    const int i = threadIdx.x;
+    if (i < B) {
+        const int t = next_tok[i];
+        const int g = st.gen[i] + 1, L = st.kv_len[i] + 1;
+        const int f = (g >= st.target[i]) || (eos >= 0 && t == eos);
+        st.tok[i] = t; st.gen[i] = g; st.kv_len[i] = L; st.fin[i] = f;
+        if (f) atomicAdd(&s_fin, 1);                       // integer sums: order does not matter
+        atomicAdd(&s_ctx, (unsigned long long)L);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        st.scalars[S_NFIN] = s_fin;
+        *reinterpret_cast<int64_t *>(st.scalars + S_SUMCTX) = (int64_t)s_ctx;
+        const int step = st.scalars[S_STEP] + 1;
+        st.scalars[S_STEP] = step;
+        if (rep) { rep->live = B; rep->n_fin = s_fin; rep->sum_ctx = (int64_t)s_ctx; rep->n_free = st.scalars[S_NFREE]; rep->step = step; }
+    }
+}
+
+// Stable compaction, part 1: new slot of every survivor, finished slots' pages
+// back on the free stack (slot order, page order), per-slot integer state moved.
+__global__ __launch_bounds__(kBlk) void compact_state_kernel(StateArrays st, int B)
+{
+    const int j = threadIdx.x;
+    const int f = (j < B) ? st.fin[j] : 1;
+    const int keep = (j < B && !f) ? 1 : 0;
+    const int L = (j < B) ? st.kv_len[j] : 0;
+    const int freed = (j < B && f) ? (L + st.P - 1) / st.P : 0;
+    int n_keep, n_freed;
+    const int dst = block_exclusive_scan(keep, n_keep);
+    const int off = block_exclusive_scan(freed, n_freed);
+    const int n_free = st.scalars[S_NFREE];
+    for (int p = 0; p < freed; ++p) st.free_stack[n_free + off + p] = st.page_table[(int64_t)j * st.max_pages + p];
+    int v0 = 0, v1 = 0, v2 = 0, v3 = 0, v4 = 0;
+    if (keep) { v0 = st.seq_id[j]; v1 = st.tok[j]; v2 = st.kv_len[j]; v3 = st.gen[j]; v4 = st.target[j]; }
+    if (j < B) st.tmp[j] = keep ? dst : -1;
+    __syncthreads();
+    if (keep) { st.seq_id[dst] = v0; st.tok[dst] = v1; st.kv_len[dst] = v2; st.gen[dst] = v3; st.target[dst] = v4; st.fin[dst] = 0; }
+    if (j == 0) { st.scalars[S_NFREE] = n_free + n_freed; st.scalars[S_LIVE] = n_keep; st.scalars[S_NFIN] = 0; }
+}
+
+// part 2: survivors' page-table rows -> their new row in the spare table (old kv_len read from tmp side array)
+__global__ void compact_rows_out_kernel(StateArrays st, int B)
+{
+    const int j = blockIdx.x;
+    const int d = st.tmp[j];
+    if (d < 0) return;
+    const int np = (st.kv_len[d] + st.P - 1) / st.P;     // state already moved: slot d holds j's length
+    for (int p = threadIdx.x; p < np; p += blockDim.x)
+        st.page_table_tmp[(int64_t)d * st.max_pages + p] = st.page_table[(int64_t)j * st.max_pages + p];
+}
+
+// part 3: spare table -> page table for the surviving rows
+__global__ void compact_rows_back_kernel(StateArrays st)
+{
+    const int d = blockIdx.x;
+    if (d >= st.scalars[S_LIVE]) return;
+    const int np = (st.kv_len[d] + st.P - 1) / st.P;
+    for (int p = threadIdx.x; p < np; p += blockDim.x)
+        st.page_table[(int64_t)d * st.max_pages + p] = st.page_table_tmp[(int64_t)d * st.max_pages + p];
+}
+
+// contiguous [n_tokens, hkv, d] <-> pages of one slot, 16 bytes per thread
+__global__ void kv_copy_kernel(KvLayout kv, int layer, const int32_t *pt_row, uint16_t *k, uint16_t *v, int n_tokens,
+                               int to_pool)
+{
+    const int vec_per_tok = kv.hkv * kv.d / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)n_tokens * vec_per_tok) return;
+    const int t = (int)(i / vec_per_tok), r = (int)(i % vec_per_tok);
+    const int head = r / (kv.d / 8), e = (r % (kv.d / 8)) * 8;
+    const int page = pt_row[t / kv.P];
+    const int64_t pool_off = page * kv.page_elems() + ((int64_t)head * kv.P + (t % kv.P)) * kv.d + e;
+    const int64_t flat = ((int64_t)t * kv.hkv + head) * kv.d + e;
+    uint4 *pk = reinterpret_cast<uint4 *>(kv.pool + kv.base(layer, 0) + pool_off);
+    uint4 *pv = reinterpret_cast<uint4 *>(kv.pool + kv.base(layer, 1) + pool_off);
+    uint4 *fk = reinterpret_cast<uint4 *>(k + flat), *fv = reinterpret_cast<uint4 *>(v + flat);
+    if (to_pool) { *pk = *fk; *pv = *fv; } else { *fk = *pk; *fv = *pv; }
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
+// Whole pool <- pseudo-random values of roughly unit variance (profiling fill:
+// timing only, never compared with anything).  Sum of four uniform bytes, centred.
+__global__ void kv_fill_kernel(uint4 *pool, int64_t n_vec, uint32_t seed)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float f[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint32_t h = mix32((uint32_t)(i * 8 + j * 2 + e) ^ mix32(seed + (uint32_t)(i >> 29)));
+                const float u = (float)(h & 255u) + (float)((h >> 8) & 255u) + (float)((h >> 16) & 255u) + (float)(h >> 24);
+                f[e] = (u - 510.0f) * (1.0f / 147.8f);   // var of one byte = 5461.25; 4 bytes -> sd 147.8
+            }
+            w[j] = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
+        }
+        pool[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_pool_init(const StateArrays &st, int n_pages, hipStream_t s)
+{
+    const int n = n_pages > 8 ? n_pages : 8;
+    pool_init_kernel<<<(n + 255) / 256, 256, 0, s>>>(st, n_pages);
+    return hipGetLastError();
+}
+
+hipError_t launch_admit(const StateArrays &st, int live, int n, hipStream_t s)
+{
+    admit_kernel<<<1, kBlk, 0, s>>>(st, live, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipStream_t s)
+{
+    plan_step_kernel<<<1, kBlk, 0, s>>>(st, B, chunk_tokens);
+    return hipGetLastError();
+}
+
+hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s)
+{
+    embed_kernel<<<B, 256, 0, s>>>(table, H, tok, x);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const StateArrays &st,
+                              const float *rope_cs, int B, hipStream_t s)
+{
+    rope_append_kernel<<<B, 256, 0, s>>>(qkv, ldq, hq, kv, layer, st, rope_cs);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmax(const float *logits, int B, int n, int base, int32_t *out_idx, float *out_val, hipStream_t s)
+{
+    if (B <= 0) return hipSuccess;
+    argmax_kernel<<<B, kBlk, 0, s>>>(logits, n, base, out_idx, out_val);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, int eos, void *report_dev, hipStream_t s)
+{
+    finish_kernel<<<1, kBlk, 0, s>>>(st, next_tok, B, eos, reinterpret_cast<ReportDev *>(report_dev));
+    return hipGetLastError();
+}
+
+hipError_t launch_compact(const StateArrays &st, int B, hipStream_t s)
+{
+    compact_state_kernel<<<1, kBlk, 0, s>>>(st, B);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    compact_rows_out_kernel<<<B, 256, 0, s>>>(st, B);
+    compact_rows_back_kernel<<<B, 256, 0, s>>>(st);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, uint16_t *k, uint16_t *v, int n_tokens,
+                          int to_pool, hipStream_t s)
+{
+    if (n_tokens <= 0) return hipSuccess;
+    const int64_t n = (int64_t)n_tokens * (kv.hkv * kv.d / 8);
+    kv_copy_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(kv, layer, pt_row, k, v, n_tokens, to_pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_fill(const KvLayout &kv, int n_layers, uint64_t seed, hipStream_t s)
+{
+    const int64_t n_vec = (int64_t)n_layers * 2 * kv.n_pages * kv.page_elems() / 8;
+    kv_fill_kernel<<<4096, 256, 0, s>>>(reinterpret_cast<uint4 *>(kv.pool), n_vec, (uint32_t)(seed ^ (seed >> 32)));
+    return hipGetLastError();
+}
+
+}  // namespace pat

@@ -1,0 +1,281 @@
+"""Step-level parity of the HIP decode path (through the C ABI) against the CPU oracle:
+logits within tolerance, tokens / integer state / compaction bit-exact, appended K/V
+within one bf16 step, allocator invariants, error paths."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import pat_inputs as pi
+from gpu_util import (DEV, bf16_close, check_logits, make_decoder, make_oracle_decoder, oracle_admit)
+from oracle import bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _pat():
+    import paper_2605_23945_amd as p
+    return p
+
+
+def _gpu_step(dec, B, vs):
+    logits = torch.empty(B, vs, device=DEV)
+    nxt = torch.empty(B, dtype=torch.int32, device=DEV)
+    rep = dec.pat_decode_step(True, nxt, logits)
+    return logits.cpu().numpy(), nxt.cpu().numpy(), rep
+
+
+def _check_pages(dec, P):
+    st = dec.pat_get_state()
+    pt, free = dec.pat_get_pages()
+    used = []
+    for i in range(st["live"]):
+        used += pt[i, : -(-int(st["kv_len"][i]) // P)].tolist()
+    assert len(used) == len(set(used)), "a page is owned twice"
+    assert not (set(used) & set(free.tolist())), "a page is both owned and free"
+    assert len(set(free.tolist())) == len(free)
+    assert len(used) + len(free) == dec.req.n_pages
+    return st
+
+
+def _rollout_parity(shard, n_seq, prompt_len, targets, page_tokens=64, max_steps=10**9, check_kv=True):
+    """Free-running greedy rollout on both sides with compaction whenever a sequence finishes."""
+    pat = _pat()
+    req = pi.rollout_requests(shard, n_seq, prompt_len, steps=1)
+    req["target"] = np.asarray(targets, np.int32)
+    cap = int(req["target"].max()) + 1
+    dec = make_decoder(shard, max(n_seq, 1), int(req["kv_len"].max()) + cap + 1,
+                       int((req["kv_len"] + req["target"]).sum()) + 64 * n_seq, page_tokens)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    odec = make_oracle_decoder(shard)
+    oracle_admit(odec, shard, req, range(n_seq), cap)
+    worst, step = 0.0, 0
+    while len(odec.tok) and step < max_steps:
+        B = len(odec.tok)
+        ref_logits, ref_next, ref_nf = odec.step()
+        got_logits, got_next, rep = _gpu_step(dec, B, shard.vocab)
+        worst = max(worst, check_logits(got_logits, ref_logits))
+        assert np.array_equal(got_next, ref_next), f"step {step}: tokens differ"
+        assert rep.live_batch == B and rep.n_finished == ref_nf and rep.sum_context == int(odec.kv_len.sum())
+        st = dec.pat_get_state()
+        for k_gpu, k_orc in (("seq_id", "seq_id"), ("token", "tok"), ("kv_len", "kv_len"), ("gen", "gen"),
+                             ("target", "target"), ("fin", "fin")):
+            assert np.array_equal(st[k_gpu], getattr(odec, k_orc)), k_gpu
+        if ref_nf:
+            before = {}
+            for j in range(B):
+                if not odec.fin[j]:
+                    before[int(odec.seq_id[j])] = [tuple(t.cpu() for t in dec.pat_kv_read(j, l, int(odec.kv_len[j])))
+                                                   for l in range(shard.n_layers)]
+            nb = odec.compact()
+            assert dec.pat_kv_compact() == nb
+            st = _check_pages(dec, page_tokens)
+            assert st["live"] == nb
+            for k_gpu, k_orc in (("seq_id", "seq_id"), ("token", "tok"), ("kv_len", "kv_len"), ("gen", "gen"),
+                                 ("target", "target")):
+                assert np.array_equal(st[k_gpu], getattr(odec, k_orc)), k_gpu
+            for j in range(nb):        # the survivors' logical K/V is byte-identical after the move
+                for l in range(shard.n_layers):
+                    k, v = dec.pat_kv_read(j, l, int(odec.kv_len[j]))
+                    kb, vb = before[int(odec.seq_id[j])][l]
+                    assert torch.equal(k.cpu(), kb) and torch.equal(v.cpu(), vb)
+        step += 1
+    if check_kv and len(odec.tok):
+        for j in range(len(odec.tok)):
+            L = int(odec.kv_len[j])
+            for l in range(shard.n_layers):
+                k, v = dec.pat_kv_read(j, l, L)
+                L0 = L - int(odec.gen[j])
+                assert np.array_equal(bits(k)[:L0], odec.kc[j][l][:L0])          # the prompt's K/V are untouched
+                for got, ref in ((bits(k)[L0:], odec.kc[j][l][L0:L]), (bits(v)[L0:], odec.vc[j][l][L0:L])):
+                    frac, close = bf16_close(got, ref)
+                    assert close and frac > 0.98, (frac, close)
+    dec.close()
+    return worst, step
+
+
+def test_tiny_config_32_greedy_steps():
+    """Configuration 1: 2 layers, hidden 256, 4 heads x 64, batch 8, KV lengths U[16,128], 32 steps."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    worst, steps = _rollout_parity(shard, 8, (16, 128), [33] * 8, max_steps=32)
+    assert steps == 32
+    print(f"tiny: worst logit error {worst:.2e} x scale")
+
+
+def test_tiny_rollout_with_compaction_until_empty():
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    targets = [3, 1, 7, 3, 12, 1, 5, 9, 2, 12, 4]
+    worst, steps = _rollout_parity(shard, len(targets), (1, 150), targets, page_tokens=16)
+    assert steps == 12
+
+
+def test_no_prompt_and_page_boundaries():
+    """kv_len = 0 (nothing cached) and lengths that sit exactly on page boundaries."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    pat = _pat()
+    req = pi.rollout_requests(shard, 5, (1, 2), steps=20)
+    req["kv_len"] = np.array([0, 15, 16, 17, 32], np.int32)
+    dec = make_decoder(shard, 5, 64, 400, 16)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    odec = make_oracle_decoder(shard)
+    oracle_admit(odec, shard, req, range(5), 21)
+    for _ in range(20):
+        ref_logits, ref_next, _ = odec.step()
+        got_logits, got_next, _ = _gpu_step(dec, 5, shard.vocab)
+        check_logits(got_logits, ref_logits)
+        assert np.array_equal(got_next, ref_next)
+    _check_pages(dec, 16)
+    dec.close()
+
+
+@pytest.mark.parametrize("tp,rank", [(2, 1), (4, 3)])
+def test_tp_shard_of_tiny_model(tp, rank):
+    """A TP shard is the shard's shapes; its vocabulary slice reports global token ids."""
+    m = pi.CONFIGS["tiny_tp1"]["shard"].model
+    shard = pi.shard_of(m, tp, rank)
+    worst, _ = _rollout_parity(shard, 3, (10, 90), [4, 2, 4])
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(8, 1, 128), (8, 2, 64), (4, 2, 128)])
+def test_grouped_query_shapes(hq, hkv, d):
+    m = pi.ModelShape(2, 256, hq, hkv, d, 512, 512)
+    _rollout_parity(pi.shard_of(m, 1, 0), 4, (30, 300), [3, 3, 2, 3])
+
+
+def test_long_context_many_chunks_and_ragged_batch():
+    """Lengths spanning several attention chunks and pages with a ragged tail; batch 19 = two batch tiles."""
+    m = pi.ModelShape(1, 256, 4, 2, 64, 512, 512)
+    shard = pi.shard_of(m, 1, 0)
+    n = 19
+    req = pi.rollout_requests(shard, n, (1, 1500), steps=2)
+    _rollout_parity(shard, n, (1, 1500), [2] * n, check_kv=False)
+
+
+def test_determinism_bitwise():
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    pat = _pat()
+    outs = []
+    for _ in range(2):
+        req = pi.rollout_requests(shard, 6, (16, 400), steps=3)
+        dec = make_decoder(shard, 6, 512, 4096)
+        pat.admit_synthetic(dec, shard, req, DEV)
+        acc = [_gpu_step(dec, 6, shard.vocab)[0] for _ in range(3)]
+        outs.append(np.stack(acc))
+        dec.close()
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_eos_token_finishes_a_sequence():
+    """With eos enabled the finish flag follows the token the device chose."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    pat = _pat()
+    req = pi.rollout_requests(shard, 3, (8, 40), steps=6)
+    odec = make_oracle_decoder(shard)
+    oracle_admit(odec, shard, req, range(3), 8)
+    _, first, _ = odec.step()
+    eos = int(first[1])                                  # the token sequence 1 produces first
+    odec = make_oracle_decoder(shard, eos=eos)
+    oracle_admit(odec, shard, req, range(3), 8)
+    dec = make_decoder(shard, 3, 64, 512, 16, eos=eos)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    _, ref_next, nf = odec.step()
+    _, got_next, rep = _gpu_step(dec, 3, shard.vocab)
+    assert np.array_equal(got_next, ref_next) and rep.n_finished == nf >= 1
+    assert np.array_equal(dec.pat_get_state()["fin"], odec.fin)
+    assert dec.pat_kv_compact() == odec.compact()
+    assert np.array_equal(dec.pat_get_state()["seq_id"], odec.seq_id)
+    dec.close()
+
+
+def test_error_paths_leave_state_untouched():
+    pat = _pat()
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    bad = pat.make_cfg(shard, 4, 64, 256, page_tokens=48)
+    with pytest.raises(pat.PatError):
+        pat.Decoder(bad, DEV)
+    bad = pat.make_cfg(pi.ShardShape(shard.model, 3, 0), 4, 64, 256)          # 4 heads not divisible by 3
+    with pytest.raises(pat.PatError):
+        pat.Decoder(bad, DEV)
+    dec = make_decoder(shard, 4, 64, 64, 16)                                  # pool: 4 + 4 pages of 16 tokens
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_step()
+    assert e.value.code == pat.binding.PAT_ESTATE                              # empty batch
+    req = pi.rollout_requests(shard, 6, (10, 20), steps=2)
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_admit(req["seq_id"], req["token"], req["kv_len"], req["target"])
+    assert e.value.code == pat.binding.PAT_ENOMEM                              # 6 > max_batch
+    big = dict(req); big["kv_len"] = np.full(6, 40, np.int32)
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_admit(big["seq_id"][:4], big["token"][:4], big["kv_len"][:4], big["target"][:4])
+    assert e.value.code == pat.binding.PAT_ENOMEM                              # 12 pages > 8
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_admit(req["seq_id"][:1], req["token"][:1], np.array([60], np.int32), np.array([10], np.int32))
+    assert e.value.code == pat.binding.PAT_EINVAL                              # 70 > max_seq_len
+    assert dec.pat_get_state()["live"] == 0 and len(dec.pat_get_pages()[1]) == dec.req.n_pages
+    idx = [0, 1]
+    pat.admit_synthetic(dec, shard, req, DEV, idx=idx)
+    dec.pat_decode_step(); dec.pat_decode_step()                              # both reach their target of 2
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_step()
+    assert e.value.code == pat.binding.PAT_ESTATE                              # finished slots present
+    assert dec.pat_kv_compact() == 0
+    assert len(dec.pat_get_pages()[1]) == dec.req.n_pages                      # every page came back
+    dec.close()
+
+
+def test_page_exhaustion_is_reported_before_the_step():
+    pat = _pat()
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    dec = make_decoder(shard, 2, 256, 32, 16)                                  # 2 + 2 pages
+    req = pi.rollout_requests(shard, 2, (16, 16), steps=100)
+    pat.admit_synthetic(dec, shard, req, DEV)                                  # one page each, both full
+    dec.pat_decode_step()                                                      # takes the two spare pages
+    for _ in range(15):
+        dec.pat_decode_step()
+    with pytest.raises(pat.PatError) as e:
+        dec.pat_decode_step()                                                  # would need two more pages
+    assert e.value.code == pat.binding.PAT_ENOMEM
+    assert np.array_equal(dec.pat_get_state()["kv_len"], [32, 32])
+    dec.close()
+
+
+def test_7b_shape_two_layers_sampled_rows():
+    """True 7B widths (hidden 4096, 32 heads x 128, FFN 11008, vocab 32000) at reduced depth;
+    batch 40 (three batch tiles, ragged), oracle on sampled rows (rows are independent)."""
+    shard = pi.CONFIGS["7b_tp1"]["shard"].with_layers(2)
+    pat = _pat()
+    n = 40
+    req = pi.rollout_requests(shard, n, (128, 1024), steps=4)
+    dec = make_decoder(shard, n, 1100, int(req["kv_len"].sum()) + 64 * n + 256)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    rows = [0, 15, 16, 39, int(np.argmax(req["kv_len"])), int(np.argmin(req["kv_len"]))]
+    odec = make_oracle_decoder(shard)
+    oracle_admit(odec, shard, req, rows, 4)
+    for step in range(2):
+        ref_logits, ref_next, _ = odec.step()
+        got_logits, got_next, _ = _gpu_step(dec, n, shard.vocab)
+        w = check_logits(got_logits[rows], ref_logits)
+        assert np.array_equal(got_next[rows], ref_next)
+        print(f"7b x2 layers step {step}: worst {w:.2e} x scale")
+    dec.close()
+
+
+def test_70b_gqa_tp8_shape_two_layers_sampled_rows():
+    """70B-style TP=8 shard widths: hidden 8192, 8 query heads sharing 1 KV head, FFN slice 3584,
+    vocabulary slice 16032 of rank 3 (global ids offset)."""
+    shard = pi.shard_of(pi.CONFIGS["70b_tp8"]["shard"].model, 8, 3).with_layers(2)
+    pat = _pat()
+    n = 5
+    req = pi.rollout_requests(shard, n, (256, 2048), steps=3)
+    dec = make_decoder(shard, n, 2100, int(req["kv_len"].sum()) + 64 * n + 256)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    rows = [0, 4]
+    odec = make_oracle_decoder(shard)
+    oracle_admit(odec, shard, req, rows, 3)
+    ref_logits, ref_next, _ = odec.step()
+    got_logits, got_next, _ = _gpu_step(dec, n, shard.vocab)
+    check_logits(got_logits[rows], ref_logits)
+    assert np.array_equal(got_next[rows], ref_next)
+    assert np.all(got_next >= 3 * shard.vocab) and np.all(got_next < 4 * shard.vocab)
+    dec.close()
