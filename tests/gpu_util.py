@@ -12,10 +12,14 @@ from oracle import Oracle, OracleDecoder, bits
 DEV = "cuda:0"
 
 # Logit tolerance of the benchmark spec: max-abs <= 2e-2 x the logit scale (std of the
-# oracle's logits of that row).  DESIGN_TOL is what the arithmetic of this implementation
-# should achieve (split-bf16 operands, fp32 accumulation): two orders tighter.
+# oracle's logits of that row).  The arithmetic of this implementation (split-bf16 operands,
+# fp32 accumulation) is good to about 1e-4 of the scale; what is left is the KV append: a k or v
+# element within that distance of a bf16 rounding boundary rounds the other way than in the
+# float64 oracle (one bf16 step = 2^-8 of the element), and with only a few cached tokens a
+# single such element moves the logits by up to ~1e-3 of the scale.  DESIGN_TOL bounds that.
 TOL = 2e-2
-DESIGN_TOL = 5e-4
+DESIGN_TOL = 5e-3
+KV_ABS_TOL = 5e-4
 
 
 def widen(b: np.ndarray) -> np.ndarray:
@@ -74,8 +78,13 @@ def check_logits(got: np.ndarray, ref: np.ndarray, tol=TOL, design_tol=DESIGN_TO
 
 
 def bf16_close(a_bits: np.ndarray, b_bits: np.ndarray):
-    """(fraction bit-identical, all within one bf16 step)."""
+    """(fraction bit-identical, all within one bf16 step).
+
+    The fp32 k, v that get rounded already differ from the oracle's by the path's accumulated
+    arithmetic error (KV_ABS_TOL, relative to the tensor's scale), which matters
+    for elements that cancel to nearly zero; so the allowance is one bf16 step of the value
+    plus KV_ABS_TOL of the tensor's rms."""
     same = a_bits == b_bits
     a, b = widen(a_bits), widen(b_bits)
-    step = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + 1e-38
+    step = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + KV_ABS_TOL * float(np.sqrt(np.mean(b * b)))
     return float(same.mean()), bool(np.all(np.abs(a - b) <= step))
