@@ -196,8 +196,12 @@ int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, 
 /* y [b, n] (+)= x W^T with W in streaming layout.  mode 0: y = ; mode 1: y += ;
  * mode 2: W is a gate/up interleave of [2f, k]; y_hi/y_lo receive
  * silu(gate)*up as packed split-bf16 activations [b, f] (y unused). */
+/* scratch: device, 256-byte aligned, pat_op_gemm_scratch_bytes(n, k, b) bytes (0 = none
+ * needed, then it may be NULL): room for the partial sums when K is split across
+ * workgroups; they are added in slice order. */
+int64_t pat_op_gemm_scratch_bytes(int32_t n, int32_t k, int32_t b);
 int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b,
-                float *y, int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *hip_stream);
+                float *y, int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *scratch, void *hip_stream);
 /* RMSNorm of x [b, h] with gains g [h] bf16 into packed split-bf16 activations. */
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo,
                         void *hip_stream);

@@ -179,16 +179,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
     }
 }
 
-// One workgroup per sequence: merge its chunk partials head by head and write
+// 64-thread workgroups over (sequence, group of heads): merge the chunk partials and write
 // the attention output as packed split-bf16 activations for the O projection.
 template <int D>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+__global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a)
 {
     constexpr int LPT = D / 8;
-    const int b = blockIdx.x;
+    const int b = blockIdx.y;
     const int ce0 = a.chunk_start[b], nch = a.chunk_start[b + 1] - ce0;
     const int KS = a.hq * D / 32;
-    for (int idx = threadIdx.x; idx < a.hq * LPT; idx += blockDim.x) {
+    for (int idx = blockIdx.x * 64 + threadIdx.x; idx < a.hq * LPT; idx += gridDim.x * 64) {
         const int head = idx / LPT, seg = idx - head * LPT;
         float M = -INFINITY;
         for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((int64_t)(ce0 + c) * a.hq + head) * 2]);
@@ -244,8 +244,9 @@ hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s)
 hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    if (a.kv.d == 128) attn_merge_kernel<128><<<a.B, 256, 0, s>>>(a);
-    else if (a.kv.d == 64) attn_merge_kernel<64><<<a.B, 256, 0, s>>>(a);
+    const dim3 grid((a.hq * (a.kv.d / 8) + 63) / 64, a.B);
+    if (a.kv.d == 128) attn_merge_kernel<128><<<grid, 64, 0, s>>>(a);
+    else if (a.kv.d == 64) attn_merge_kernel<64><<<grid, 64, 0, s>>>(a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

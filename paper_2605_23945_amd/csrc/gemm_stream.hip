@@ -2,16 +2,23 @@
 // projections of the decode step (QKV, O, gate/up, down, vocabulary head).
 //
 // The step is bound by reading W once from HBM.  W is kept in a streaming layout
-// (see pat_dev.h): the 16 rows x K strip a workgroup owns is one contiguous run,
+// (see pat_dev.h): the 16 rows x K strip of a row tile is one contiguous run,
 // every wave load is a full 1 KiB line-aligned block of 16-byte vectors, and each
 // vector is directly the A operand of v_mfma_f32_16x16x32_bf16.  The live batch
 // (padded to 16) is the MFMA's N dimension, so B <= 16 costs the same bytes as
 // B = 1.  Activations are fp32 split into two bf16 terms (hi + lo), giving
 // fp32-class products on the bf16 matrix cores; accumulation is fp32.
 //
-// One workgroup = 8 waves = one 16-row tile; the waves split K in round-robin
-// chunks (wave-level split-K) and their partial tiles are summed through LDS in
-// wave order, so results do not depend on timing.
+// Two kernels share the layouts:
+//  - gemm_xs_kernel (live batch <= 32): activation-stationary; each wave keeps its
+//    K slice of the activations in registers and streams row tiles past it
+//    (wave-level split-K, partial tiles summed through LDS in wave order).
+//  - gemm_tiled_kernel (live batch 33..256): the batch is a real dense dimension;
+//    a workgroup owns 128 weight rows, stages the activations of two k-steps in
+//    LDS for its four waves and keeps 2 x NB accumulator tiles per wave.
+// The tiled kernel can also split K across workgroups; the slice partials go to a
+// scratch tensor and gemm_reduce_kernel adds them in slice order, so results never
+// depend on timing.
 #include "pat_dev.h"
 #include "pat_kernels.h"
 
@@ -19,8 +26,6 @@ namespace pat {
 
 namespace {
 
-constexpr int kGemmWaves = 8;
-constexpr int kGemmThreads = kGemmWaves * kWave;
 
 __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c)
 {
@@ -30,14 +35,14 @@ __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c)
 
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + expf(-z)); }
 
-// Epilogue for one summed float4 = 4 consecutive output features of batch row b.
+// Epilogue for a float4 = 4 consecutive output features (rows 16 rt + 4 quad ..) of batch row b.
 template <int MODE>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int l, int b, float4 v)
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int quad, int b, float4 v)
 {
     if (b >= a.B) return;
     if (MODE == kGemmSwiGLU) {
         // rows alternate gate, up: (g f0, u f0, g f0+1, u f0+1)
-        const int f0 = rt * 8 + (l >> 4) * 2;
+        const int f0 = rt * 8 + quad * 2;
         if (2 * f0 < a.n_valid) {
             uint16_t h0, l0, h1, l1;
             split_bf16(silu(v.x) * v.y, h0, l0);
@@ -47,7 +52,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int l, 
             reinterpret_cast<uint32_t *>(a.ylo)[off >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
     } else {
-        const int n = rt * 16 + (l >> 4) * 4;
+        const int n = rt * 16 + quad * 4;
         float *yp = a.y + (int64_t)b * a.ldy + n;
         if (n + 3 < a.n_valid) {
             float4 o = v;
@@ -65,117 +70,208 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int l, 
     }
 }
 
-// NB: 16-row batch tiles per wave (live batch <= 16 NB); U: k-steps per chunk;
-// PF: prefetch the next chunk's operands while the matrix cores work on this one.
-template <int NB, int U, int MODE, bool PF>
-__global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(GemmArgs a)
+// K-slice partial of (row tile rt, quad, batch row b): part[kb][b][n_tiles*16]
+__device__ __forceinline__ void store_partial(const GemmArgs &a, int kb, int rt, int quad, int b, float4 v)
 {
-    extern __shared__ float4 red[];   // [kGemmWaves][NB][64]
+    if (b >= a.B) return;
+    const int64_t ldp = (int64_t)a.n_tiles * 16;
+    *reinterpret_cast<float4 *>(a.part + ((int64_t)kb * a.B + b) * ldp + rt * 16 + quad * 4) = v;
+}
+
+// ---- live batch <= 32: activation-stationary streaming ------------------------------
+// A workgroup owns a group of row tiles over the whole of K.  Each of its 16 waves owns a
+// contiguous K range and walks it in passes of UK k-steps: for a pass it loads its
+// split-bf16 activation fragments into registers once and streams every row tile of the
+// group past them, so activations are fetched once per workgroup instead of once per row
+// tile, nearly every load in flight is a 1 KiB block of the HBM weight stream, and the
+// waves run free of barriers while they stream.  A wave accumulates its partial tiles in
+// its own LDS slots; after the last pass one barrier lets wave i sum tile i's partials in
+// wave order.  No cross-workgroup reduction, no atomics: a fixed summation order.
+constexpr int kXsWaves = 16;
+
+template <int NB, int UK, int TB, int MODE>
+__global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
+{
+    extern __shared__ float4 red[];   // [TB][kXsWaves][NB][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int KS = a.KS;
-    const int n_full = KS / U;        // chunks of U k-steps; the ragged rest is done by one wave
+    const int KS = a.KS, Rg = a.Rg;
+    const int rg = blockIdx.x;
+    const int per = (KS + kXsWaves - 1) / kXsWaves;                  // k-steps owned by a wave
+    const int kown0 = wave * per, kown1 = min(KS, kown0 + per);
+    const int rt0 = (int)((int64_t)rg * a.n_tiles / Rg), rt1 = (int)((int64_t)(rg + 1) * a.n_tiles / Rg);
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-    bool bvalid[NB];
+    for (int tb0 = rt0; tb0 < rt1; tb0 += TB) {
+        const int nt = min(TB, rt1 - tb0);
+        for (int kw0 = kown0, pass = 0; kw0 < kown1; kw0 += UK, ++pass) {
+            const int kw1 = min(kown1, kw0 + UK);
+            // Loads are unconditional 16-byte vectors at constant offsets from one base: the
+            // window of UK k-steps starts at kbase (pulled back so it stays inside the matrix,
+            // KS >= UK); steps outside [kw0, kw1) are nulled through the weights.  Batch rows past
+            // the live batch re-read the last live row: their output columns are never stored, and
+            // a matrix-core output column depends on its own activation column only.
+            const int kbase = max(0, min(kw0, KS - UK));
+            bool kvalid[UK];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) bvalid[nb] = (nb * 16 + (lane & 15)) < a.B;
-
-    for (int rt = blockIdx.x; rt < a.n_tiles; rt += gridDim.x) {
-        floatx4_t acc[NB];
+            for (int u = 0; u < UK; ++u) kvalid[u] = (kbase + u >= kw0) && (kbase + u < kw1);
+            uint4 xh[UK][NB], xl[UK][NB];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-
-        const uint4 *wp = a.w + (int64_t)rt * KS * 64 + lane;
-        const uint4 *xh = a.xhi + lane, *xl = a.xlo + lane;
-
-        if (PF) {
-            uint4 wc[U], hc[U][NB], lc[U][NB];
-            auto load_chunk = [&](int c, uint4 (&w)[U], uint4 (&h)[U][NB], uint4 (&l)[U][NB]) {
-                const uint4 *wq = wp + c * (U * 64);
+            for (int nb = 0; nb < NB; ++nb) {
+                const int rsel = min(lane & 15, a.B - 1 - nb * 16);
+                const uint4 *ph = a.xhi + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
+                const uint4 *pl = a.xlo + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
 #pragma unroll
-                for (int u = 0; u < U; ++u) w[u] = wq[u * 64];
+                for (int u = 0; u < UK; ++u) { xh[u][nb] = ph[u * 64]; xl[u][nb] = pl[u * 64]; }
+            }
+            for (int i = 0; i < nt; ++i) {
+                const uint4 *wp = a.w + ((int64_t)(tb0 + i) * KS + kbase) * 64 + lane;
+                uint4 w[UK];
+#pragma unroll
+                for (int u = 0; u < UK; ++u) w[u] = wp[u * 64];
+#pragma unroll
+                for (int u = 0; u < UK; ++u) if (!kvalid[u]) w[u] = zero4;
+                floatx4_t acc_h[NB], acc_l[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) { acc_h[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; acc_l[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+                for (int u = 0; u < UK; ++u) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        acc_h[nb] = mfma16(w[u], xh[u][nb], acc_h[nb]);
+                        acc_l[nb] = mfma16(w[u], xl[u][nb], acc_l[nb]);
+                    }
+                }
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const uint4 *hq = xh + (nb * KS + c * U) * 64, *lq = xl + (nb * KS + c * U) * 64;
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        h[u][nb] = bvalid[nb] ? hq[u * 64] : zero4;
-                        l[u][nb] = bvalid[nb] ? lq[u * 64] : zero4;
-                    }
-                }
-            };
-            int c = wave;
-            if (c < n_full) load_chunk(c, wc, hc, lc);
-            for (; c < n_full; c += kGemmWaves) {
-                uint4 wn[U], hn[U][NB], ln[U][NB];
-                const bool more = c + kGemmWaves < n_full;
-                if (more) load_chunk(c + kGemmWaves, wn, hn, ln);
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        acc[nb] = mfma16(wc[u], hc[u][nb], acc[nb]);
-                        acc[nb] = mfma16(wc[u], lc[u][nb], acc[nb]);
-                    }
-                }
-                if (more) {
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        wc[u] = wn[u];
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) { hc[u][nb] = hn[u][nb]; lc[u][nb] = ln[u][nb]; }
-                    }
-                }
-            }
-        } else {
-            for (int c = wave; c < n_full; c += kGemmWaves) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int ks = c * U + u;
-                    const uint4 w = wp[ks * 64];
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const uint4 h = bvalid[nb] ? xh[(nb * KS + ks) * 64] : zero4;
-                        const uint4 l = bvalid[nb] ? xl[(nb * KS + ks) * 64] : zero4;
-                        acc[nb] = mfma16(w, h, acc[nb]);
-                        acc[nb] = mfma16(w, l, acc[nb]);
-                    }
+                    float4 v = make_float4(acc_h[nb][0] + acc_l[nb][0], acc_h[nb][1] + acc_l[nb][1],
+                                           acc_h[nb][2] + acc_l[nb][2], acc_h[nb][3] + acc_l[nb][3]);
+                    float4 *slot = &red[((i * kXsWaves + wave) * NB + nb) * 64 + lane];    // this wave's own slot
+                    if (pass > 0) { const float4 o = *slot; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                    *slot = v;
                 }
             }
         }
-        // ragged tail of K (KS not a multiple of U)
-        if (wave == (n_full % kGemmWaves)) {
-            for (int ks = n_full * U; ks < KS; ++ks) {
-                const uint4 w = wp[ks * 64];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const uint4 h = bvalid[nb] ? xh[(nb * KS + ks) * 64] : zero4;
-                    const uint4 l = bvalid[nb] ? xl[(nb * KS + ks) * 64] : zero4;
-                    acc[nb] = mfma16(w, h, acc[nb]);
-                    acc[nb] = mfma16(w, l, acc[nb]);
-                }
-            }
-        }
-
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            red[(wave * NB + nb) * 64 + lane] = make_float4(acc[nb][0], acc[nb][1], acc[nb][2], acc[nb][3]);
         __syncthreads();
-
-        // D tile layout: lane l holds rows (l/16)*4 .. +3 of column l%16 = 4 consecutive
-        // output features of one batch row.  Partials are summed in wave order.
-        for (int e = threadIdx.x; e < NB * 64; e += kGemmThreads) {
-            const int nb = e >> 6, l = e & 63;
-            float4 v = red[nb * 64 + l];
+        if (wave < nt) {
+            // D tile layout: lane l holds rows (l/16)*4 .. +3 of column l%16 = 4 consecutive
+            // output features of one batch row.  Waves that own no k-steps left no partial.
+            const int rt = tb0 + wave;
+            const int nw = min(kXsWaves, (KS + per - 1) / per);
 #pragma unroll
-            for (int w = 1; w < kGemmWaves; ++w) {
-                const float4 t = red[(w * NB + nb) * 64 + l];
-                v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            for (int nb = 0; nb < NB; ++nb) {
+                float4 v = red[((wave * kXsWaves + 0) * NB + nb) * 64 + lane];
+                for (int ww = 1; ww < nw; ++ww) {
+                    const float4 t = red[((wave * kXsWaves + ww) * NB + nb) * 64 + lane];
+                    v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+                }
+                gemm_epilogue<MODE>(a, rt, lane >> 4, nb * 16 + (lane & 15), v);
             }
-            gemm_epilogue<MODE>(a, rt, l, nb * 16 + (l & 15), v);
+        }
+        if (tb0 + TB < rt1) __syncthreads();
+    }
+}
+
+// ---- live batch 33..256 -------------------------------------------------------------
+constexpr int kTileWaves = 4, kTileMT = 2, kTileS = 2;
+constexpr int kTileRows = kTileWaves * kTileMT;     // row tiles per workgroup (= 128 rows)
+
+template <int NB, int MODE>
+__global__ __launch_bounds__(kTileWaves * 64) void gemm_tiled_kernel(GemmArgs a)
+{
+    extern __shared__ uint4 xs[];     // [2 (hi, lo)][kTileS][NB][64]
+    constexpr int NV = 2 * kTileS * NB * 64;          // vectors per stage
+    constexpr int VPT = NV / (kTileWaves * 64);       // per thread
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KS = a.KS, kb = blockIdx.y;
+    const int ks0 = (int)((int64_t)kb * KS / a.Kb), ks1 = (int)((int64_t)(kb + 1) * KS / a.Kb);
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const int rt0 = blockIdx.x * kTileRows + wave * kTileMT;
+
+    floatx4_t acc[kTileMT][NB];
+#pragma unroll
+    for (int mt = 0; mt < kTileMT; ++mt)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    // stage vector v = ((half * S + s) * NB + nb) * 64 + ln  <-  x{hi,lo}[(nb * KS + ks + s) * 64 + ln]
+    auto fetch_x = [&](int ks, uint4 (&r)[VPT]) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = i * (kTileWaves * 64) + tid;
+            const int ln = v & 63, nb = (v >> 6) % NB, s = ((v >> 6) / NB) % kTileS, half = (v >> 6) / (NB * kTileS);
+            const int bsel = min(nb * 16 + (ln & 15), a.B - 1);           // clamped: always a live row (the buffer holds ceil(B/16) tiles)
+            const uint4 *src = half ? a.xlo : a.xhi;
+            r[i] = src[((int64_t)(bsel >> 4) * KS + min(ks + s, ks1 - 1)) * 64 + (ln >> 4) * 16 + (bsel & 15)];
+        }
+    };
+    auto fetch_w = [&](int ks, uint4 (&w)[kTileS][kTileMT]) {
+#pragma unroll
+        for (int s = 0; s < kTileS; ++s)
+#pragma unroll
+            for (int mt = 0; mt < kTileMT; ++mt) {
+                const bool ok = (ks + s < ks1) && (rt0 + mt < a.n_tiles);
+                const uint4 v = a.w[((int64_t)min(rt0 + mt, a.n_tiles - 1) * KS + min(ks + s, ks1 - 1)) * 64 + lane];
+                w[s][mt] = ok ? v : zero4;
+            }
+    };
+
+    uint4 xr[VPT], wr[kTileS][kTileMT];
+    fetch_x(ks0, xr);
+    fetch_w(ks0, wr);
+    for (int ks = ks0; ks < ks1; ks += kTileS) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) xs[i * (kTileWaves * 64) + tid] = xr[i];
+        uint4 wc[kTileS][kTileMT];
+#pragma unroll
+        for (int s = 0; s < kTileS; ++s)
+#pragma unroll
+            for (int mt = 0; mt < kTileMT; ++mt) wc[s][mt] = wr[s][mt];
+        __syncthreads();
+        if (ks + kTileS < ks1) { fetch_x(ks + kTileS, xr); fetch_w(ks + kTileS, wr); }
+#pragma unroll
+        for (int s = 0; s < kTileS; ++s) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const uint4 h = xs[((0 * kTileS + s) * NB + nb) * 64 + lane];
+                const uint4 l = xs[((1 * kTileS + s) * NB + nb) * 64 + lane];
+#pragma unroll
+                for (int mt = 0; mt < kTileMT; ++mt) {
+                    acc[mt][nb] = mfma16(wc[s][mt], h, acc[mt][nb]);
+                    acc[mt][nb] = mfma16(wc[s][mt], l, acc[mt][nb]);
+                }
+            }
         }
         __syncthreads();
     }
+
+#pragma unroll
+    for (int mt = 0; mt < kTileMT; ++mt) {
+        if (rt0 + mt >= a.n_tiles) continue;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float4 v = make_float4(acc[mt][nb][0], acc[mt][nb][1], acc[mt][nb][2], acc[mt][nb][3]);
+            if (a.Kb == 1) gemm_epilogue<MODE>(a, rt0 + mt, lane >> 4, nb * 16 + (lane & 15), v);
+            else store_partial(a, kb, rt0 + mt, lane >> 4, nb * 16 + (lane & 15), v);
+        }
+    }
+}
+
+// Sum of the K-slice partials in slice order, then the epilogue.  One thread per
+// (batch row, 4 consecutive output features).
+template <int MODE>
+__global__ void gemm_reduce_kernel(GemmArgs a)
+{
+    const int quads = a.n_tiles * 4;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)a.B * quads) return;
+    const int b = (int)(i / quads), q = (int)(i % quads);
+    const int64_t ldp = (int64_t)a.n_tiles * 16;
+    float4 v = *reinterpret_cast<const float4 *>(a.part + (int64_t)b * ldp + q * 4);
+    for (int kb = 1; kb < a.Kb; ++kb) {
+        const float4 t = *reinterpret_cast<const float4 *>(a.part + ((int64_t)kb * a.B + b) * ldp + q * 4);
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+    gemm_epilogue<MODE>(a, q >> 2, q & 3, b, v);
 }
 
 // one thread per 16-byte vector of the packed matrix
@@ -254,31 +350,86 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const
     }
 }
 
-template <int NB, int U, bool PF>
-hipError_t launch_gemm_nb(const GemmArgs &a, int mode, hipStream_t s)
+template <int NB, int UK, int TB>
+hipError_t launch_xs(const GemmArgs &a, int mode, hipStream_t s)
 {
-    const int grid = a.n_tiles;
-    const size_t lds = (size_t)kGemmWaves * NB * 64 * sizeof(float4);
+    const unsigned grid = (unsigned)a.Rg;
+    constexpr size_t lds = (size_t)TB * kXsWaves * NB * 64 * sizeof(float4);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     switch (mode) {
-    case kGemmStore: gemm_stream_kernel<NB, U, kGemmStore, PF><<<grid, kGemmThreads, lds, s>>>(a); break;
-    case kGemmAccum: gemm_stream_kernel<NB, U, kGemmAccum, PF><<<grid, kGemmThreads, lds, s>>>(a); break;
-    default: gemm_stream_kernel<NB, U, kGemmSwiGLU, PF><<<grid, kGemmThreads, lds, s>>>(a); break;
+    case kGemmStore: gemm_xs_kernel<NB, UK, TB, kGemmStore><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    case kGemmAccum: gemm_xs_kernel<NB, UK, TB, kGemmAccum><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    default: gemm_xs_kernel<NB, UK, TB, kGemmSwiGLU><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <int NB>
+hipError_t launch_tiled(const GemmArgs &a, int mode, hipStream_t s)
+{
+    const dim3 grid((a.n_tiles + kTileRows - 1) / kTileRows, a.Kb);
+    const size_t lds = (size_t)2 * kTileS * NB * 64 * sizeof(uint4);
+    switch (mode) {
+    case kGemmStore: gemm_tiled_kernel<NB, kGemmStore><<<grid, kTileWaves * 64, lds, s>>>(a); break;
+    case kGemmAccum: gemm_tiled_kernel<NB, kGemmAccum><<<grid, kTileWaves * 64, lds, s>>>(a); break;
+    default: gemm_tiled_kernel<NB, kGemmSwiGLU><<<grid, kTileWaves * 64, lds, s>>>(a); break;
     }
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gemm(const GemmArgs &a, int mode, hipStream_t s)
+static int g_target_wgs = 256;   // one resident workgroup per compute unit
+void gemm_set_compute_units(int n) { if (n > 0) g_target_wgs = n; }
+
+GemmPlan gemm_plan(int n_tiles, int KS, int B)
 {
-    if (a.B <= 0 || a.n_tiles <= 0) return hipSuccess;
+    GemmPlan p{1, 1};
+    if (B <= 32 && KS >= 8) {
+        p.Kb = 1;                                              // a workgroup walks all of K itself
+        p.Rg = n_tiles < g_target_wgs ? n_tiles : g_target_wgs;
+    } else {
+        // enough workgroups to cover the chip, at least 8 k-steps per slice
+        const int groups = (n_tiles + kTileRows - 1) / kTileRows;
+        int kb = 1;
+        while (groups * kb < 384 && KS / (kb * 2) >= 8 && kb < 16) kb *= 2;
+        p.Kb = kb;
+        p.Rg = groups;
+    }
+    return p;
+}
+
+hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
+{
+    if (a0.B <= 0 || a0.n_tiles <= 0) return hipSuccess;
+    GemmArgs a = a0;
+    const GemmPlan p = gemm_plan(a.n_tiles, a.KS, a.B);
+    a.Kb = p.Kb; a.Rg = p.Rg;
+    if (a.Kb > 1 && a.part == nullptr) return hipErrorInvalidValue;
     const int nb = (a.B + 15) / 16;
-    if (nb <= 1) return launch_gemm_nb<1, 4, true>(a, mode, s);
-    if (nb <= 2) return launch_gemm_nb<2, 2, true>(a, mode, s);
-    if (nb <= 4) return launch_gemm_nb<4, 2, false>(a, mode, s);
-    if (nb <= 8) return launch_gemm_nb<8, 2, false>(a, mode, s);
-    if (nb <= 16) return launch_gemm_nb<16, 2, false>(a, mode, s);
-    return hipErrorInvalidValue;
+    if (nb <= 1 && a.KS >= 8) return launch_xs<1, 8, 8>(a, mode, s);
+    if (nb <= 2 && a.KS >= 8) return launch_xs<2, 4, 4>(a, mode, s);
+    hipError_t e;
+    if (nb <= 4) e = launch_tiled<4>(a, mode, s);
+    else if (nb <= 8) e = launch_tiled<8>(a, mode, s);
+    else if (nb <= 16) e = launch_tiled<16>(a, mode, s);
+    else return hipErrorInvalidValue;
+    if (e != hipSuccess || a.Kb == 1) return e;
+    const int64_t n = (int64_t)a.B * a.n_tiles * 4;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    switch (mode) {
+    case kGemmStore: gemm_reduce_kernel<kGemmStore><<<blocks, 256, 0, s>>>(a); break;
+    case kGemmAccum: gemm_reduce_kernel<kGemmAccum><<<blocks, 256, 0, s>>>(a); break;
+    default: gemm_reduce_kernel<kGemmSwiGLU><<<blocks, 256, 0, s>>>(a); break;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s)

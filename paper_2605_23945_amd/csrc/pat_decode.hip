@@ -28,7 +28,7 @@ struct Shard {
 };
 
 struct WorkLayout {   // byte offsets inside the work arena
-    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, part_acc, part_ml, logits, next_tok, best_val, rope, report;
+    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
     int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, tmp;
     int64_t total;
     int64_t max_chunks;
@@ -143,6 +143,19 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     w->b_hi = take(packed_x_bytes(MB, kb));
     w->b_lo = take(packed_x_bytes(MB, kb));
     w->qkv = take((int64_t)MB * s.qkv_rows * 4);
+    {   // scratch for K-slice partial sums of the projections: the largest any (matrix, batch) needs
+        const int mats[5][2] = {{s.qkv_rows / 16, s.H / 32}, {s.H / 16, s.hq * s.d / 32}, {2 * s.F / 16, s.H / 32},
+                                {s.H / 16, s.F / 32}, {s.Vs / 16, s.H / 32}};
+        int64_t need = 0;
+        for (auto &mt : mats)
+            for (int B : {16, 32, 64, 128, 256}) {
+                const int b = std::min(B, MB);
+                const int kb = gemm_plan(mt[0], mt[1], b).Kb;
+                if (kb > 1) need = std::max(need, (int64_t)kb * b * mt[0] * 16 * 4);
+            }
+        w->gemm_part = take(std::max<int64_t>(need, 256));
+
+    }
     w->max_chunks = c->kv_token_budget / kMinChunk + 2 * (int64_t)MB;
     w->part_acc = take(w->max_chunks * s.hq * s.d * 4);
     w->part_ml = take(w->max_chunks * s.hq * 2 * 4);
@@ -303,6 +316,10 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
         if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
         if (e != hipSuccess) return die("rotary table upload", e);
     }
+    {
+        hipDeviceProp_t prop; int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) gemm_set_compute_units(prop.multiProcessorCount);
+    }
     e = launch_pool_init(c->st, s.n_pages, c->stream);
     if (e != hipSuccess) return die("pool init", e);
     *out = c;
@@ -435,6 +452,7 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     float *logits = logits_dev ? logits_dev : at<float>(W, w.logits);
     int32_t *next_tok = next_tok_dev ? next_tok_dev : at<int32_t>(W, w.next_tok);
     char *Wb = at<char>(c->bufs.weights, 0);
+    float *gpart = at<float>(W, w.gemm_part);
 
     { TimeScope t(c, 2); PAT_HIP(c, launch_plan_step(c->st, B, C, st)); }
     { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
@@ -449,29 +467,29 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
         char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wqkv), s.qkv_rows / 16, s.H / 32, a_hi, a_lo, B, qkv, s.qkv_rows, s.qkv_rows, nullptr, nullptr, 0};
+            GemmArgs g{(const uint4 *)(L + c->wt.wqkv), s.qkv_rows / 16, s.H / 32, a_hi, a_lo, B, qkv, s.qkv_rows, s.qkv_rows, nullptr, nullptr, 0, gpart, 1, 1};
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
         }
         { TimeScope t(c, 2); PAT_HIP(c, launch_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st, at<float>(W, w.rope), B, st)); }
         aa.layer = l;
         { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wo), s.H / 16, s.hq * s.d / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0};
+            GemmArgs g{(const uint4 *)(L + c->wt.wo), s.H / 16, s.hq * s.d / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0, gpart, 1, 1};
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wgu), 2 * s.F / 16, s.H / 32, a_hi, a_lo, B, nullptr, 0, 2 * s.F, b_hi, b_lo, s.F / 32};
+            GemmArgs g{(const uint4 *)(L + c->wt.wgu), 2 * s.F / 16, s.H / 32, a_hi, a_lo, B, nullptr, 0, 2 * s.F, b_hi, b_lo, s.F / 32, gpart, 1, 1};
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
         }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wd), s.H / 16, s.F / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0};
+            GemmArgs g{(const uint4 *)(L + c->wt.wd), s.H / 16, s.F / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0, gpart, 1, 1};
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
     }
     { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
     {
-        GemmArgs g{(const uint4 *)(Wb + c->wt.wlm), s.Vs / 16, s.H / 32, a_hi, a_lo, B, logits, s.Vs, s.Vs, nullptr, nullptr, 0};
+        GemmArgs g{(const uint4 *)(Wb + c->wt.wlm), s.Vs / 16, s.H / 32, a_hi, a_lo, B, logits, s.Vs, s.Vs, nullptr, nullptr, 0, gpart, 1, 1};
         TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
     }
     { TimeScope t(c, 2); PAT_HIP(c, launch_argmax(logits, B, s.Vs, s.vocab0, next_tok, at<float>(W, w.best_val), st)); }
@@ -680,14 +698,25 @@ int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, 
     return launch_pack_act(x, b, k, (uint4 *)xhi, (uint4 *)xlo, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
+int64_t pat_op_gemm_scratch_bytes(int32_t n, int32_t k, int32_t b)
+{
+    if (n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256) return -1;
+    const int kb = gemm_plan(cdiv(n, 16), k / 32, b).Kb;
+    return kb > 1 ? (int64_t)kb * b * cdiv(n, 16) * 16 * 4 : 0;
+}
+
 int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b, float *y,
-                int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *stream)
+                int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *scratch, void *stream)
 {
     if (!w_packed || !xhi || !xlo || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256 || mode < 0 || mode > 2) return PAT_EINVAL;
     if (mode == kGemmSwiGLU) { if (!y_hi || !y_lo || n % 2 || (n / 2) % 32) return PAT_EINVAL; }
     else if (!y || ldy < n) return PAT_EINVAL;
     GemmArgs g{(const uint4 *)w_packed, cdiv(n, 16), k / 32, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, n,
-               (uint4 *)y_hi, (uint4 *)y_lo, mode == kGemmSwiGLU ? n / 2 / 32 : 0};
+               (uint4 *)y_hi, (uint4 *)y_lo, mode == kGemmSwiGLU ? n / 2 / 32 : 0, nullptr, 1, 1};
+    if (pat_op_gemm_scratch_bytes(n, k, b) > 0) {
+        if (!scratch || ((uintptr_t)scratch & (kAlign - 1))) return PAT_EINVAL;
+        g.part = (float *)scratch;
+    }
     return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 

@@ -17,7 +17,13 @@ struct GemmArgs {
     int ldy, n_valid;          // row stride of y, number of real output columns
     uint4 *yhi, *ylo;          // SwiGLU: packed split-bf16 output [b_tiles][KS_out][64]
     int KS_out;
+    float *part;               // scratch for K-slice partials [Kb][B][n_tiles * 16], or NULL
+    int Kb, Rg;                // set by launch_gemm from gemm_plan
 };
+// How a [16 n_tiles, 32 KS] projection at live batch B is cut: K slices across workgroups and row groups.
+struct GemmPlan { int Kb, Rg; };
+GemmPlan gemm_plan(int n_tiles, int KS, int B);
+void gemm_set_compute_units(int n);
 
 hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s);
 hipError_t launch_pack_act(const float *x, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);

@@ -93,38 +93,34 @@ __global__ void embed_kernel(const uint16_t *table, int H, const int32_t *tok, f
     }
 }
 
-// One workgroup per sequence.  Position = tokens already cached.  q heads are
-// rotated in place (fp32); the new k (rotated) and v are rounded to bf16
-// (nearest-even) and written into the slot's page.
-__global__ __launch_bounds__(256) void rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
-                                                          StateArrays st, const float *rope_cs)
+// One 64-thread workgroup per (sequence, head of q | k | v).  Position = tokens
+// already cached.  q heads are rotated in place (fp32); the new k (rotated) and v
+// are rounded to bf16 (nearest-even) and written into the slot's page.
+__global__ __launch_bounds__(64) void rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
+                                                         StateArrays st, const float *rope_cs)
 {
-    const int b = blockIdx.x;
+    const int b = blockIdx.y, head = blockIdx.x;
     const int D = kv.d, half = D / 2, hkv = kv.hkv, P = kv.P;
     const int pos = st.kv_len[b];
-    const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
-    float *row = qkv + (int64_t)b * ldq;
-    const float *cs = rope_cs + (int64_t)pos * D;   // [half][2]
-    uint16_t *kdst = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + (int64_t)(pos % P) * D;
-    uint16_t *vdst = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + (int64_t)(pos % P) * D;
-    const int n_pairs = (hq + hkv) * half;
-    for (int i = threadIdx.x; i < n_pairs; i += blockDim.x) {
-        const int head = i / half, j = i - head * half;
-        const float c = cs[2 * j], s = cs[2 * j + 1];
-        float *p = row + head * D;
-        const float x0 = p[j], x1 = p[j + half];
-        const float r0 = x0 * c - x1 * s, r1 = x0 * s + x1 * c;
-        if (head < hq) {
-            p[j] = r0; p[j + half] = r1;
-        } else {
-            uint16_t *d = kdst + (int64_t)(head - hq) * P * D;
-            d[j] = f32_to_bf16(r0); d[j + half] = f32_to_bf16(r1);
+    float *p = qkv + (int64_t)b * ldq + head * D;
+    if (head < hq + hkv) {
+        const float *cs = rope_cs + (int64_t)pos * D;   // [half][2]
+        uint16_t *kd = nullptr;
+        if (head >= hq) {
+            const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
+            kd = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + ((int64_t)(head - hq) * P + (pos % P)) * D;
         }
-    }
-    const float *vsrc = row + (hq + hkv) * D;
-    for (int i = threadIdx.x; i < hkv * D; i += blockDim.x) {
-        const int head = i / D, e = i - head * D;
-        vdst[(int64_t)head * P * D + e] = f32_to_bf16(vsrc[i]);
+        for (int j = threadIdx.x; j < half; j += 64) {
+            const float c = cs[2 * j], s = cs[2 * j + 1];
+            const float x0 = p[j], x1 = p[j + half];
+            const float r0 = x0 * c - x1 * s, r1 = x0 * s + x1 * c;
+            if (kd) { kd[j] = f32_to_bf16(r0); kd[j + half] = f32_to_bf16(r1); }
+            else { p[j] = r0; p[j + half] = r1; }
+        }
+    } else {
+        const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
+        uint16_t *vd = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + ((int64_t)(head - hq - hkv) * P + (pos % P)) * D;
+        for (int e = threadIdx.x; e < D; e += 64) vd[e] = f32_to_bf16(p[e]);
     }
 }
 
@@ -304,7 +300,7 @@ hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B,
 hipError_t launch_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const StateArrays &st,
                               const float *rope_cs, int B, hipStream_t s)
 {
-    rope_append_kernel<<<B, 256, 0, s>>>(qkv, ldq, hq, kv, layer, st, rope_cs);
+    rope_append_kernel<<<dim3(hq + 2 * kv.hkv, B), 64, 0, s>>>(qkv, ldq, hq, kv, layer, st, rope_cs);
     return hipGetLastError();
 }
 
