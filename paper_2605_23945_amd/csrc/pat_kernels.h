@@ -21,7 +21,7 @@ struct GemmArgs {
     int Kb, Rg;                // set by launch_gemm from gemm_plan
 };
 // How a [16 n_tiles, 32 KS] projection at live batch B is cut: K slices across workgroups and row groups.
-struct GemmPlan { int Kb, Rg; };
+struct GemmPlan { int Kb, Rg, NB, MT; };
 GemmPlan gemm_plan(int n_tiles, int KS, int B);
 void gemm_set_compute_units(int n);
 
