@@ -40,7 +40,37 @@ template <int MODE>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int quad, int b, float4 v)
 {
     if (b >= a.B) return;
-    if (MODE == kGemmSwiGLU) {
+    if (MODE == kGemmQKV) {
+        const int n = rt * 16 + quad * 4;                 // stored row: 4 | n, so a quad never straddles heads
+        if (n >= a.n_valid) return;
+        const int D = a.kv.d, half = D >> 1, P = a.kv.P;
+        const int head = n / D, p0 = n - head * D;
+        const int pos = a.kv_len[b];
+        if (head < a.hq + a.kv.hkv) {
+            // stored rows (p0, p0+1) are natural (j0, j0 + D/2); (p0+2, p0+3) are (j0+1, j0+1 + D/2)
+            const int j0 = p0 >> 1;
+            const float4 cs = *reinterpret_cast<const float4 *>(a.rope_cs + ((int64_t)pos * half + j0) * 2);
+            const float r00 = v.x * cs.x - v.y * cs.y, r01 = v.x * cs.y + v.y * cs.x;
+            const float r10 = v.z * cs.z - v.w * cs.w, r11 = v.z * cs.w + v.w * cs.z;
+            if (head < a.hq) {
+                float *q = a.y + (int64_t)b * a.ldy + head * D;
+                *reinterpret_cast<float2 *>(q + j0) = make_float2(r00, r10);
+                *reinterpret_cast<float2 *>(q + j0 + half) = make_float2(r01, r11);
+            } else {
+                const int page = a.page_table[(int64_t)b * a.max_pages + pos / P];
+                uint16_t *kd = a.kv.pool + a.kv.base(a.layer, 0) + page * a.kv.page_elems() +
+                               ((int64_t)(head - a.hq) * P + (pos % P)) * D;
+                *reinterpret_cast<uint32_t *>(kd + j0) = (uint32_t)f32_to_bf16(r00) | ((uint32_t)f32_to_bf16(r10) << 16);
+                *reinterpret_cast<uint32_t *>(kd + j0 + half) = (uint32_t)f32_to_bf16(r01) | ((uint32_t)f32_to_bf16(r11) << 16);
+            }
+        } else {
+            const int page = a.page_table[(int64_t)b * a.max_pages + pos / P];
+            uint16_t *vd = a.kv.pool + a.kv.base(a.layer, 1) + page * a.kv.page_elems() +
+                           ((int64_t)(head - a.hq - a.kv.hkv) * P + (pos % P)) * D + p0;
+            *reinterpret_cast<uint2 *>(vd) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                                                        (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+        }
+    } else if (MODE == kGemmSwiGLU) {
         // rows alternate gate, up: (g f0, u f0, g f0+1, u f0+1)
         const int f0 = rt * 8 + quad * 2;
         if (2 * f0 < a.n_valid) {
@@ -79,7 +109,7 @@ __device__ __forceinline__ void store_partial(const GemmArgs &a, int kb, int rt,
 }
 
 // ---- live batch <= 32: activation-stationary streaming ------------------------------
-// A workgroup owns a group of row tiles over the whole of K.  Each of its 16 waves owns a
+// A workgroup owns a group of row tiles over the whole of K.  Each of its waves (8 or 16) owns a
 // contiguous K range and walks it in passes of UK k-steps: for a pass it loads its
 // split-bf16 activation fragments into registers once and streams every row tile of the
 // group past them, so activations are fetched once per workgroup instead of once per row
@@ -87,9 +117,8 @@ __device__ __forceinline__ void store_partial(const GemmArgs &a, int kb, int rt,
 // waves run free of barriers while they stream.  A wave accumulates its partial tiles in
 // its own LDS slots; after the last pass one barrier lets wave i sum tile i's partials in
 // wave order.  No cross-workgroup reduction, no atomics: a fixed summation order.
-constexpr int kXsWaves = 16;
 
-template <int NB, int UK, int TB, int MODE>
+template <int NB, int UK, int TB, int kXsWaves, int MODE>
 __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 {
     extern __shared__ float4 red[];   // [TB][kXsWaves][NB][64]
@@ -118,10 +147,12 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int rsel = min(lane & 15, a.B - 1 - nb * 16);
-                const uint4 *ph = a.xhi + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
-                const uint4 *pl = a.xlo + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
+                {
+                    const uint4 *ph = a.xhi + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
+                    const uint4 *pl = a.xlo + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
 #pragma unroll
-                for (int u = 0; u < UK; ++u) { xh[u][nb] = ph[u * 64]; xl[u][nb] = pl[u * 64]; }
+                    for (int u = 0; u < UK; ++u) { xh[u][nb] = ph[u * 64]; xl[u][nb] = pl[u * 64]; }
+                }
             }
             for (int i = 0; i < nt; ++i) {
                 const uint4 *wp = a.w + ((int64_t)(tb0 + i) * KS + kbase) * 64 + lane;
@@ -397,7 +428,7 @@ __global__ void gemm_reduce_kernel(GemmArgs a)
 
 // one thread per 16-byte vector of the packed matrix
 __global__ void pack_weight_kernel(const uint16_t *w, const uint16_t *w2, int n, int k, int KS, int64_t n_vec,
-                                   uint4 *packed)
+                                   uint4 *packed, int rope_rows, int d)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_vec) return;
@@ -410,6 +441,10 @@ __global__ void pack_weight_kernel(const uint16_t *w, const uint16_t *w2, int n,
     const uint16_t *src = w;
     int srow = row;
     if (w2 != nullptr) { src = (row & 1) ? w2 : w; srow = row >> 1; }
+    if (row < rope_rows) {                       // rotary partners (j, j + d/2) become stored neighbours
+        const int head = row / d, p = row - head * d;
+        srow = head * d + ((p & 1) ? (p >> 1) + (d >> 1) : (p >> 1));
+    }
     uint4 v = make_uint4(0, 0, 0, 0);
     if (srow < n) v = *reinterpret_cast<const uint4 *>(src + (int64_t)srow * k + kk);
     packed[i] = v;
@@ -471,23 +506,25 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const
     }
 }
 
-template <int NB, int UK, int TB>
+template <int NB, int UK, int TB, int kXsWaves>
 hipError_t launch_xs(const GemmArgs &a, int mode, hipStream_t s)
 {
     const unsigned grid = (unsigned)a.Rg;
     constexpr size_t lds = (size_t)TB * kXsWaves * NB * 64 * sizeof(float4);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     switch (mode) {
-    case kGemmStore: gemm_xs_kernel<NB, UK, TB, kGemmStore><<<grid, kXsWaves * 64, lds, s>>>(a); break;
-    case kGemmAccum: gemm_xs_kernel<NB, UK, TB, kGemmAccum><<<grid, kXsWaves * 64, lds, s>>>(a); break;
-    default: gemm_xs_kernel<NB, UK, TB, kGemmSwiGLU><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    case kGemmStore: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmStore><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    case kGemmAccum: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmAccum><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    case kGemmQKV: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmQKV><<<grid, kXsWaves * 64, lds, s>>>(a); break;
+    default: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmSwiGLU><<<grid, kXsWaves * 64, lds, s>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -500,6 +537,7 @@ hipError_t launch_tiled(const GemmArgs &a, int mode, hipStream_t s)
     switch (mode) {
     case kGemmStore: gemm_tiled_kernel<NB, MT, kGemmStore><<<grid, kTileWaves * 64, lds, s>>>(a); break;
     case kGemmAccum: gemm_tiled_kernel<NB, MT, kGemmAccum><<<grid, kTileWaves * 64, lds, s>>>(a); break;
+    case kGemmQKV: gemm_tiled_kernel<NB, MT, kGemmQKV><<<grid, kTileWaves * 64, lds, s>>>(a); break;
     default: gemm_tiled_kernel<NB, MT, kGemmSwiGLU><<<grid, kTileWaves * 64, lds, s>>>(a); break;
     }
     return hipGetLastError();
@@ -516,12 +554,14 @@ hipError_t launch_xl(const GemmArgs &a, int mode, hipStream_t s)
         hipError_t e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     switch (mode) {
     case kGemmStore: gemm_xl_kernel<WS, kGemmStore><<<grid, kXlWaves * 64, lds, s>>>(a); break;
     case kGemmAccum: gemm_xl_kernel<WS, kGemmAccum><<<grid, kXlWaves * 64, lds, s>>>(a); break;
+    case kGemmQKV: gemm_xl_kernel<WS, kGemmQKV><<<grid, kXlWaves * 64, lds, s>>>(a); break;
     default: gemm_xl_kernel<WS, kGemmSwiGLU><<<grid, kXlWaves * 64, lds, s>>>(a); break;
     }
     return hipGetLastError();
@@ -535,7 +575,7 @@ void gemm_set_compute_units(int n) { if (n > 0) g_target_wgs = n; }
 GemmPlan gemm_plan(int n_tiles, int KS, int B)
 {
     GemmPlan p{1, 1, 4, 1};
-    if (B <= 32 && KS >= 8) {
+    if (B <= 32 && KS >= 16) {
         p.Kb = 1;                                              // a workgroup walks all of K itself
         p.Rg = n_tiles < g_target_wgs ? n_tiles : g_target_wgs;
     } else if (KS >= kXlP) {
@@ -564,8 +604,9 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     const GemmPlan p = gemm_plan(a.n_tiles, a.KS, a.B);
     a.Kb = p.Kb; a.Rg = p.Rg;
     if (a.Kb > 1 && a.part == nullptr) return hipErrorInvalidValue;
-    if (a.B <= 16 && a.KS >= 8) return launch_xs<1, 8, 8>(a, mode, s);
-    if (a.B <= 32 && a.KS >= 8) return launch_xs<2, 4, 4>(a, mode, s);
+    // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
+    if (a.B <= 16 && a.KS >= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
+    if (a.B <= 32 && a.KS >= 16) return launch_xs<2, 8, 8, 8>(a, mode, s);
     hipError_t e;
     if (a.KS >= kXlP) e = p.MT == 1 ? launch_xl<1>(a, mode, s) : p.MT == 2 ? launch_xl<2>(a, mode, s) : launch_xl<4>(a, mode, s);
     else e = launch_tiled<4, 1>(a, mode, s);
@@ -575,6 +616,7 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     switch (mode) {
     case kGemmStore: gemm_reduce_kernel<kGemmStore><<<blocks, 256, 0, s>>>(a); break;
     case kGemmAccum: gemm_reduce_kernel<kGemmAccum><<<blocks, 256, 0, s>>>(a); break;
+    case kGemmQKV: gemm_reduce_kernel<kGemmQKV><<<blocks, 256, 0, s>>>(a); break;
     default: gemm_reduce_kernel<kGemmSwiGLU><<<blocks, 256, 0, s>>>(a); break;
     }
     return hipGetLastError();
@@ -586,7 +628,15 @@ hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int 
     const int KS = k / 32;
     const int64_t n_vec = (int64_t)((rows + 15) / 16) * KS * 64;
     const int64_t blocks = (n_vec + 255) / 256;
-    pack_weight_kernel<<<(unsigned)blocks, 256, 0, s>>>(w, w2, n, k, KS, n_vec, packed);
+    pack_weight_kernel<<<(unsigned)blocks, 256, 0, s>>>(w, w2, n, k, KS, n_vec, packed, 0, 1);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int rope_rows, int d, uint4 *packed, hipStream_t s)
+{
+    const int KS = k / 32;
+    const int64_t n_vec = (int64_t)((n + 15) / 16) * KS * 64;
+    pack_weight_kernel<<<(unsigned)((n_vec + 255) / 256), 256, 0, s>>>(w, nullptr, n, k, KS, n_vec, packed, rope_rows, d);
     return hipGetLastError();
 }
 

@@ -225,6 +225,14 @@ int flush_timing(pat_ctx *c)
     return PAT_OK;
 }
 
+GemmArgs gemm_args(const void *w, int n, int k, const uint4 *xhi, const uint4 *xlo, int B, float *y, int ldy, float *part)
+{
+    GemmArgs g{};
+    g.w = (const uint4 *)w; g.n_tiles = cdiv(n, 16); g.KS = k / 32; g.xhi = xhi; g.xlo = xlo; g.B = B;
+    g.y = y; g.ldy = ldy; g.n_valid = n; g.part = part; g.Kb = 1; g.Rg = 1;
+    return g;
+}
+
 // Batches beyond 256 rows run as groups of 256 (the weights are streamed once per group).
 hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
 {
@@ -236,6 +244,7 @@ hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
         h.xhi = g.xhi + t0 * g.KS * 64; h.xlo = g.xlo + t0 * g.KS * 64;
         if (g.y) h.y = g.y + (int64_t)b0 * g.ldy;
         if (g.yhi) { h.yhi = g.yhi + t0 * g.KS_out * 64; h.ylo = g.ylo + t0 * g.KS_out * 64; }
+        if (g.kv_len) { h.kv_len = g.kv_len + b0; h.page_table = g.page_table + (int64_t)b0 * g.max_pages; }
         hipError_t e = launch_gemm(h, mode, st);
         if (e != hipSuccess) return e;
     }
@@ -335,7 +344,7 @@ int pat_load_layer(pat_ctx *c, int32_t layer, const pat_layer_weights *w)
     char *L = at<char>(c->bufs.weights, c->wt.layer0 + c->wt.layer_stride * layer);
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
-    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wqkv, nullptr, s.qkv_rows, s.H, (uint4 *)(L + c->wt.wqkv), c->stream));
+    PAT_HIP(c, launch_pack_weight_qkv((const uint16_t *)w->wqkv, s.qkv_rows, s.H, (s.hq + s.hkv) * s.d, s.d, (uint4 *)(L + c->wt.wqkv), c->stream));
     PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wo, nullptr, s.H, s.hq * s.d, (uint4 *)(L + c->wt.wo), c->stream));
     PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wg, (const uint16_t *)w->wu, s.F, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
     PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wd, nullptr, s.H, s.F, (uint4 *)(L + c->wt.wd), c->stream));
@@ -466,30 +475,32 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     for (int l = 0; l < s.NL; ++l) {
         char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
-        {
-            GemmArgs g{(const uint4 *)(L + c->wt.wqkv), s.qkv_rows / 16, s.H / 32, a_hi, a_lo, B, qkv, s.qkv_rows, s.qkv_rows, nullptr, nullptr, 0, gpart, 1, 1};
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
+        {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
+            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart);
+            g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len;
+            g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmQKV, st));
         }
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st, at<float>(W, w.rope), B, st)); }
         aa.layer = l;
         { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wo), s.H / 16, s.hq * s.d / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0, gpart, 1, 1};
+            GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wgu), 2 * s.F / 16, s.H / 32, a_hi, a_lo, B, nullptr, 0, 2 * s.F, b_hi, b_lo, s.F / 32, gpart, 1, 1};
+            GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart);
+            g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
         }
         {
-            GemmArgs g{(const uint4 *)(L + c->wt.wd), s.H / 16, s.F / 32, b_hi, b_lo, B, x, s.H, s.H, nullptr, nullptr, 0, gpart, 1, 1};
+            GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
     }
     { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
     {
-        GemmArgs g{(const uint4 *)(Wb + c->wt.wlm), s.Vs / 16, s.H / 32, a_hi, a_lo, B, logits, s.Vs, s.Vs, nullptr, nullptr, 0, gpart, 1, 1};
+        GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart);
         TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
     }
     { TimeScope t(c, 2); PAT_HIP(c, launch_argmax(logits, B, s.Vs, s.vocab0, next_tok, at<float>(W, w.best_val), st)); }
@@ -711,8 +722,8 @@ int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, con
     if (!w_packed || !xhi || !xlo || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256 || mode < 0 || mode > 2) return PAT_EINVAL;
     if (mode == kGemmSwiGLU) { if (!y_hi || !y_lo || n % 2 || (n / 2) % 32) return PAT_EINVAL; }
     else if (!y || ldy < n) return PAT_EINVAL;
-    GemmArgs g{(const uint4 *)w_packed, cdiv(n, 16), k / 32, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, n,
-               (uint4 *)y_hi, (uint4 *)y_lo, mode == kGemmSwiGLU ? n / 2 / 32 : 0, nullptr, 1, 1};
+    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr);
+    g.yhi = (uint4 *)y_hi; g.ylo = (uint4 *)y_lo; g.KS_out = mode == kGemmSwiGLU ? n / 2 / 32 : 0;
     if (pat_op_gemm_scratch_bytes(n, k, b) > 0) {
         if (!scratch || ((uintptr_t)scratch & (kAlign - 1))) return PAT_EINVAL;
         g.part = (float *)scratch;

@@ -6,7 +6,15 @@
 namespace pat {
 
 // ---- weight-streaming projections (gemm_stream.hip) ---------------------------
-enum GemmMode { kGemmStore = 0, kGemmAccum = 1, kGemmSwiGLU = 2 };
+enum GemmMode { kGemmStore = 0, kGemmAccum = 1, kGemmSwiGLU = 2, kGemmQKV = 3 };
+
+// Paged K/V pool of all layers.
+struct KvLayout {
+    uint16_t *pool;            // [layer][2][n_pages][hkv][P][d] bf16
+    int n_pages, hkv, P, d;
+    __host__ __device__ int64_t page_elems() const { return (int64_t)hkv * P * d; }
+    __host__ __device__ int64_t base(int layer, int kv) const { return ((int64_t)layer * 2 + kv) * n_pages * page_elems(); }
+};
 
 struct GemmArgs {
     const uint4 *w;            // packed weights: [n_tiles][KS][64] vectors
@@ -17,6 +25,13 @@ struct GemmArgs {
     int ldy, n_valid;          // row stride of y, number of real output columns
     uint4 *yhi, *ylo;          // SwiGLU: packed split-bf16 output [b_tiles][KS_out][64]
     int KS_out;
+    // kGemmQKV (rows are this shard's q heads, k heads, v heads; q and k rows stored with rotary
+    // partners adjacent): rotate q and k at position kv_len[b], write q fp32 into y (natural
+    // order), append k and v as bf16 to the slot's page
+    KvLayout kv;
+    int layer, hq, max_pages;
+    const int32_t *kv_len, *page_table;
+    const float *rope_cs;      // [pos][d/2][cos, sin]
     float *part;               // scratch for K-slice partials [Kb][B][n_tiles * 16], or NULL
     int Kb, Rg;                // set by launch_gemm from gemm_plan
 };
@@ -26,18 +41,15 @@ GemmPlan gemm_plan(int n_tiles, int KS, int B);
 void gemm_set_compute_units(int n);
 
 hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s);
+// as above for a QKV matrix: within each of the first rope_rows / d heads, row p holds natural row
+// p/2 (p even) or p/2 + d/2 (p odd), so the two elements a rotation mixes are neighbours
+hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int rope_rows, int d, uint4 *packed, hipStream_t s);
 hipError_t launch_pack_act(const float *x, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);
 hipError_t launch_rmsnorm_pack(const float *x, const uint16_t *g, int b, int h, float eps, uint4 *hi, uint4 *lo,
                                hipStream_t s);
 hipError_t launch_gemm(const GemmArgs &a, int mode, hipStream_t s);
 
 // ---- attention over the paged cache (attention.hip) ----------------------------
-struct KvLayout {
-    uint16_t *pool;            // [layer][2][n_pages][hkv][P][d] bf16
-    int n_pages, hkv, P, d;
-    __host__ __device__ int64_t page_elems() const { return (int64_t)hkv * P * d; }
-    __host__ __device__ int64_t base(int layer, int kv) const { return ((int64_t)layer * 2 + kv) * n_pages * page_elems(); }
-};
 
 struct AttnArgs {
     KvLayout kv;
@@ -73,8 +85,6 @@ hipError_t launch_pool_init(const StateArrays &st, int n_pages, hipStream_t s);
 hipError_t launch_admit(const StateArrays &st, int live, int n, hipStream_t s);   // new slots' arrays already copied in
 hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipStream_t s);
 hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s);
-hipError_t launch_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const StateArrays &st,
-                              const float *rope_cs, int B, hipStream_t s);
 hipError_t launch_argmax(const float *logits, int B, int n, int base, int32_t *out_idx, float *out_val, hipStream_t s);
 hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, int eos, void *report_dev, hipStream_t s);
 hipError_t launch_compact(const StateArrays &st, int B, hipStream_t s);

@@ -1,6 +1,7 @@
 // The small kernels of the decode step: page pool and live-batch bookkeeping
 // (admit, per-step plan, finish flags, stable compaction), embedding gather,
-// rotary embedding + KV append, greedy argmax, and page <-> contiguous K/V copies.
+// greedy argmax, and page <-> contiguous K/V copies.  (Rotary embedding and the KV
+// append live in the QKV projection's epilogue.)
 // All integer bookkeeping runs in single-workgroup kernels with fixed-order block
 // scans, so page assignment and compaction are deterministic.
 #include "pat_dev.h"
@@ -90,37 +91,6 @@ __global__ void embed_kernel(const uint16_t *table, int H, const int32_t *tok, f
         float *o = x + (int64_t)b * H + k0;
         *reinterpret_cast<float4 *>(o) = make_float4(bf16lo(v.x), bf16hi(v.x), bf16lo(v.y), bf16hi(v.y));
         *reinterpret_cast<float4 *>(o + 4) = make_float4(bf16lo(v.z), bf16hi(v.z), bf16lo(v.w), bf16hi(v.w));
-    }
-}
-
-// One 64-thread workgroup per (sequence, head of q | k | v).  Position = tokens
-// already cached.  q heads are rotated in place (fp32); the new k (rotated) and v
-// are rounded to bf16 (nearest-even) and written into the slot's page.
-__global__ __launch_bounds__(64) void rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
-                                                         StateArrays st, const float *rope_cs)
-{
-    const int b = blockIdx.y, head = blockIdx.x;
-    const int D = kv.d, half = D / 2, hkv = kv.hkv, P = kv.P;
-    const int pos = st.kv_len[b];
-    float *p = qkv + (int64_t)b * ldq + head * D;
-    if (head < hq + hkv) {
-        const float *cs = rope_cs + (int64_t)pos * D;   // [half][2]
-        uint16_t *kd = nullptr;
-        if (head >= hq) {
-            const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
-            kd = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + ((int64_t)(head - hq) * P + (pos % P)) * D;
-        }
-        for (int j = threadIdx.x; j < half; j += 64) {
-            const float c = cs[2 * j], s = cs[2 * j + 1];
-            const float x0 = p[j], x1 = p[j + half];
-            const float r0 = x0 * c - x1 * s, r1 = x0 * s + x1 * c;
-            if (kd) { kd[j] = f32_to_bf16(r0); kd[j + half] = f32_to_bf16(r1); }
-            else { p[j] = r0; p[j + half] = r1; }
-        }
-    } else {
-        const int page = st.page_table[(int64_t)b * st.max_pages + pos / P];
-        uint16_t *vd = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + ((int64_t)(head - hq - hkv) * P + (pos % P)) * D;
-        for (int e = threadIdx.x; e < D; e += 64) vd[e] = f32_to_bf16(p[e]);
     }
 }
 
@@ -294,13 +264,6 @@ hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipS
 hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s)
 {
     embed_kernel<<<B, 256, 0, s>>>(table, H, tok, x);
-    return hipGetLastError();
-}
-
-hipError_t launch_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const StateArrays &st,
-                              const float *rope_cs, int B, hipStream_t s)
-{
-    rope_append_kernel<<<dim3(hq + 2 * kv.hkv, B), 64, 0, s>>>(qkv, ldq, hq, kv, layer, st, rope_cs);
     return hipGetLastError();
 }
 
