@@ -279,3 +279,90 @@ def test_70b_gqa_tp8_shape_two_layers_sampled_rows():
     assert np.array_equal(got_next[rows], ref_next)
     assert np.all(got_next >= 3 * shard.vocab) and np.all(got_next < 4 * shard.vocab)
     dec.close()
+
+
+def _sampled_rows_parity(shard, n, prompt_len, rows, steps=1, max_seq=None):
+    pat = _pat()
+    req = pi.rollout_requests(shard, n, prompt_len, steps=steps + 2)
+    dec = make_decoder(shard, n, (max_seq or prompt_len[1]) + steps + 8, int(req["kv_len"].sum()) + 64 * n + 256)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    odec = make_oracle_decoder(shard, layer_cache=False)
+    oracle_admit(odec, shard, req, rows, steps + 2)
+    worst = 0.0
+    for _ in range(steps):
+        ref_logits, ref_next, _ = odec.step()
+        got_logits, got_next, _ = _gpu_step(dec, n, shard.vocab)
+        worst = max(worst, check_logits(got_logits[rows], ref_logits))
+        assert np.array_equal(got_next[rows], ref_next)
+    dec.close()
+    return worst
+
+
+def test_7b_tp4_shard_shape_two_layers_sampled_rows():
+    """Configuration 3's shard: 8 heads x 128, FFN slice 2752, vocabulary slice 8000 (rank 2 of 4)."""
+    shard = pi.shard_of(pi.CONFIGS["7b_tp4"]["shard"].model, 4, 2).with_layers(2)
+    _sampled_rows_parity(shard, 70, (100, 600), [0, 31, 32, 69], steps=2)     # 70 rows: five batch tiles, two batch groups
+
+
+def test_13b_tp2_shard_shape_two_layers_sampled_rows():
+    """Configuration 4's shard: hidden 5120, 20 of 40 heads, FFN slice 6912, vocabulary slice 16000."""
+    shard = pi.CONFIGS["13b_tp2"]["shard"].with_layers(2)
+    _sampled_rows_parity(shard, 20, (256, 2048), [0, 15, 16, 19])
+
+
+def test_7b_full_depth_sampled_rows_in_bench_configuration():
+    """Configuration 2 at full depth (32 layers) in the launch shapes the benchmark times (live batch
+    <= 16 path and the 33..256 path): oracle on sampled rows, one step."""
+    shard = pi.CONFIGS["7b_tp1"]["shard"]
+    pat = _pat()
+    n = 48
+    req = pi.rollout_requests(shard, n, (128, 1024), steps=3)
+    dec = make_decoder(shard, n, 1100, int(req["kv_len"].sum()) + 64 * n + 256)
+    pat.admit_synthetic(dec, shard, req, DEV)
+    rows = [0, 47]
+    odec = make_oracle_decoder(shard, layer_cache=False)
+    oracle_admit(odec, shard, req, rows, 3)
+    ref_logits, ref_next, _ = odec.step()
+    got_logits, got_next, _ = _gpu_step(dec, n, shard.vocab)              # 48 rows: the batched (LDS-staged) projections
+    w1 = check_logits(got_logits[rows], ref_logits)
+    assert np.array_equal(got_next[rows], ref_next)
+    # the same two sequences alone in a fresh batch: the small-batch streaming projections
+    dec.pat_decode_reset()
+    sub = {k: v[rows] for k, v in req.items()}
+    pat.admit_synthetic(dec, shard, sub, DEV)
+    odec2 = make_oracle_decoder(shard, layer_cache=False)
+    oracle_admit(odec2, shard, req, rows, 3)
+    ref_logits2, ref_next2, _ = odec2.step()
+    got_logits2, got_next2, _ = _gpu_step(dec, 2, shard.vocab)
+    w2 = check_logits(got_logits2, ref_logits2)
+    assert np.array_equal(got_next2, ref_next2)
+    assert np.array_equal(ref_next, ref_next2)                            # rows do not depend on their batch
+    print(f"7B full depth: worst {max(w1, w2):.2e} x scale")
+    dec.close()
+
+
+def test_profile_grid_protocol():
+    """Offline-profiler sweep: B*L <= T_cap pruning, row order, mean of the timed steps, byte model."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    pat = _pat()
+    dec = make_decoder(shard, 32, 1024 + 80, 1 << 14)
+    Bs, Ls = [1, 4, 32], [16, 256, 1024]
+    rows = dec.pat_profile_grid(Bs, Ls, t_cap=1 << 13, steps=12, warmup=2, reps=2, seed=7)
+    assert len(rows) == 9
+    for i, r in enumerate(rows):
+        b, l = Bs[i // 3], Ls[i % 3]
+        assert (r["batch"], r["kv_len"], r["tp_degree"]) == (b, l, 1)
+        if b * l > (1 << 13):
+            assert r["skipped"] == 1 and r["mean_us"] == 0.0
+        else:
+            assert r["skipped"] == 0 and r["mean_us"] > 0 and r["min_us"] <= r["mean_us"]
+            assert r["sum_context"] == b * (l + 2)
+            assert abs(r["tokens_per_s"] - b / (r["mean_us"] * 1e-6)) < 1e-6 * r["tokens_per_s"]
+            m = shard.model
+            wbytes = m.n_layers * 2 * (m.hidden * shard.qkv_rows + shard.hq * m.head_dim * m.hidden + 3 * m.hidden * shard.ffn) \
+                + 2 * shard.vocab * m.hidden
+            kv = m.n_layers * 2 * shard.hkv * m.head_dim * 2 * (b * (l + 2 + 6 + 1) + b)
+            assert r["algo_bytes"] == wbytes + kv
+    assert [r["skipped"] for r in rows] == [0, 0, 0, 0, 0, 0, 0, 0, 1]
+    assert dec.pat_get_state()["live"] == 0                               # the sweep leaves an empty batch
+    dec.close()
