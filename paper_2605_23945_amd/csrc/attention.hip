@@ -8,7 +8,7 @@
 // of the G query heads that share this KV head in LDS, takes the chunk maximum,
 // then streams V once, accumulating exp(s - m) * V in registers.  It emits the
 // partial (m, l, acc); a second kernel merges a sequence's partials with the
-// online-softmax identity in chunk order, so the result is run-to-run identical.
+// online-softmax identity in a fixed order, so the result is run-to-run identical.
 #include "pat_dev.h"
 #include "pat_kernels.h"
 
@@ -65,6 +65,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
             const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
             q[g][0] = q0.x; q[g][1] = q0.y; q[g][2] = q0.z; q[g][3] = q0.w;
             q[g][4] = q1.x; q[g][5] = q1.y; q[g][6] = q1.z; q[g][7] = q1.w;
+        }
+
+        // The first batch of V rows is requested together with the K rows: a short chunk then
+        // pays one memory latency instead of two.
+        uint4 vfirst[UR];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            const int tl = u * TPR + ts;
+            vfirst[u] = make_uint4(0, 0, 0, 0);
+            if (tl < cnt) {
+                const int t = t0 + tl;
+                const int page = pt[t / P];
+                vfirst[u] = *reinterpret_cast<const uint4 *>(vbase + page * page_elems + head_off + (int64_t)(t % P) * D);
+            }
         }
 
         // ---- scores of the chunk ----
@@ -129,8 +143,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
             for (int u = 0; u < UR; ++u) {
                 const int tl = r0 + u * TPR + ts;
                 ok[u] = tl < cnt;
-                kv[u] = make_uint4(0, 0, 0, 0);
-                if (ok[u]) {
+                kv[u] = vfirst[u];
+                if (ok[u] && r0 > 0) {
                     const int t = t0 + tl;
                     const int page = pt[t / P];
                     kv[u] = *reinterpret_cast<const uint4 *>(vbase + page * page_elems + head_off + (int64_t)(t % P) * D);
@@ -179,30 +193,49 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
     }
 }
 
-// 64-thread workgroups over (sequence, group of heads): merge the chunk partials and write
-// the attention output as packed split-bf16 activations for the O projection.
+// One wave per (sequence, query head): lanes = D/8 feature segments x 64/(D/8) chunk lanes.
+// A chunk lane folds the chunks c = lane, lane + CL, ... in increasing order, then the chunk
+// lanes are combined pairwise in a fixed tree (online-softmax identity), so the result is
+// run-to-run identical.  Writes the packed split-bf16 operand of the O projection.
 template <int D>
 __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a)
 {
-    constexpr int LPT = D / 8;
-    const int b = blockIdx.y;
+    constexpr int LPT = D / 8, CL = 64 / LPT;
+    const int b = blockIdx.y, head = blockIdx.x;
+    const int lane = threadIdx.x, seg = lane % LPT, cl = lane / LPT;
     const int ce0 = a.chunk_start[b], nch = a.chunk_start[b + 1] - ce0;
     const int KS = a.hq * D / 32;
-    for (int idx = blockIdx.x * 64 + threadIdx.x; idx < a.hq * LPT; idx += gridDim.x * 64) {
-        const int head = idx / LPT, seg = idx - head * LPT;
-        float M = -INFINITY;
-        for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((int64_t)(ce0 + c) * a.hq + head) * 2]);
-        float den = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < nch; ++c) {
-            const float *mlp = a.part_ml + ((int64_t)(ce0 + c) * a.hq + head) * 2;
-            const float w = expf(mlp[0] - M);
-            den = fmaf(w, mlp[1], den);
-            const float *ap = a.part_acc + ((int64_t)(ce0 + c) * a.hq + head) * D + seg * 8;
-            const float4 p0 = *reinterpret_cast<const float4 *>(ap);
-            const float4 p1 = *reinterpret_cast<const float4 *>(ap + 4);
-            o[0] = fmaf(w, p0.x, o[0]); o[1] = fmaf(w, p0.y, o[1]); o[2] = fmaf(w, p0.z, o[2]); o[3] = fmaf(w, p0.w, o[3]);
-            o[4] = fmaf(w, p1.x, o[4]); o[5] = fmaf(w, p1.y, o[5]); o[6] = fmaf(w, p1.z, o[6]); o[7] = fmaf(w, p1.w, o[7]);
+    float M = -INFINITY, den = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int c = cl; c < nch; c += CL) {
+        const float *mlp = a.part_ml + ((int64_t)(ce0 + c) * a.hq + head) * 2;
+        const float m = mlp[0], l = mlp[1];
+        const float *ap = a.part_acc + ((int64_t)(ce0 + c) * a.hq + head) * D + seg * 8;
+        const float4 p0 = *reinterpret_cast<const float4 *>(ap);
+        const float4 p1 = *reinterpret_cast<const float4 *>(ap + 4);
+        const float Mn = fmaxf(M, m);
+        const float so = expf(M - Mn), sn = expf(m - Mn);       // M = -inf on the first chunk: so = 0
+        den = den * so + l * sn;
+        o[0] = o[0] * so + p0.x * sn; o[1] = o[1] * so + p0.y * sn; o[2] = o[2] * so + p0.z * sn; o[3] = o[3] * so + p0.w * sn;
+        o[4] = o[4] * so + p1.x * sn; o[5] = o[5] * so + p1.y * sn; o[6] = o[6] * so + p1.z * sn; o[7] = o[7] * so + p1.w * sn;
+        M = Mn;
+    }
+#pragma unroll
+    for (int off = 32; off >= LPT; off >>= 1) {
+        const float M2 = __shfl_xor(M, off, 64), den2 = __shfl_xor(den, off, 64);
+        const float Mn = fmaxf(M, M2);
+        // a chunk lane that saw no chunk carries M = -inf, den = 0: its weight is exp(-inf) = 0
+        const float s1 = (M == -INFINITY) ? 0.f : expf(M - Mn), s2 = (M2 == -INFINITY) ? 0.f : expf(M2 - Mn);
+        // the lower lane's term is added first on both sides, so both lanes of a pair hold identical sums
+        const bool low = (lane & off) == 0;
+        den = low ? den * s1 + den2 * s2 : den2 * s2 + den * s1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float o2 = __shfl_xor(o[j], off, 64);
+            o[j] = low ? o[j] * s1 + o2 * s2 : o2 * s2 + o[j] * s1;
         }
+        M = Mn;
+    }
+    if (cl == 0) {
         const float inv = 1.0f / den;
         uint16_t hh[8], ll[8];
 #pragma unroll
@@ -244,7 +277,7 @@ hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s)
 hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    const dim3 grid((a.hq * (a.kv.d / 8) + 63) / 64, a.B);
+    const dim3 grid(a.hq, a.B);
     if (a.kv.d == 128) attn_merge_kernel<128><<<grid, 64, 0, s>>>(a);
     else if (a.kv.d == 64) attn_merge_kernel<64><<<grid, 64, 0, s>>>(a);
     else return hipErrorInvalidValue;

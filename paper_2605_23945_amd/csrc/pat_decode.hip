@@ -253,14 +253,14 @@ hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
 
 int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
 {
-    // largest chunk that still gives the chip at least ~2 work items per compute unit
+    // largest chunk that still gives the chip about 8 work items per compute unit
     int best = kMinChunk;
     int64_t best_n = 0;
     for (int C : {256, 128, 64}) {
         int64_t n = 0;
         for (int i = 0; i < c->live; ++i) n += (c->kv_len[i] + 1 + C - 1) / C;
         best = C; best_n = n;
-        if (n * c->sh.hkv >= 512) break;
+        if (n * c->sh.hkv >= 2048) break;
     }
     *n_chunks = best_n;
     return best;
