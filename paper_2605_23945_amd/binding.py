@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpat_decode.so")
+LIB_PATH = os.environ.get("PAT_DECODE_LIB", os.path.join(_HERE, "libpat_decode.so"))   # override: A/B of two builds
 
 PAT_OK, PAT_EINVAL, PAT_ENOMEM, PAT_ESTATE, PAT_EHIP = 0, -1, -2, -3, -4
 
