@@ -118,6 +118,55 @@ __device__ __forceinline__ void store_partial(const GemmArgs &a, int kb, int rt,
 // its own LDS slots; after the last pass one barrier lets wave i sum tile i's partials in
 // wave order.  No cross-workgroup reduction, no atomics: a fixed summation order.
 
+// One pass of a wave: U k-steps [kw0, kw0 + U) against row tiles [tb0, tb0 + nt).  The wave's
+// activation fragments of the pass are loaded once and stay in registers.  All loads are
+// unconditional 16-byte vectors at constant offsets from one base.  Batch rows past the live batch
+// re-read the last live row: their output columns are never stored, and a matrix-core output
+// column depends on its own activation column only.
+template <int NB, int U, int WAVES>
+__device__ __forceinline__ void xs_pass(const GemmArgs &a, int lane, int wave, int kw0, int tb0, int nt, bool first,
+                                        float4 *red)
+{
+    const int KS = a.KS;
+    uint4 xh[U][NB], xl[U][NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int rsel = min(lane & 15, a.B - 1 - nb * 16);
+        const uint4 *ph = a.xhi + (nb * KS + kw0) * 64 + (lane >> 4) * 16 + rsel;
+        const uint4 *pl = a.xlo + (nb * KS + kw0) * 64 + (lane >> 4) * 16 + rsel;
+#pragma unroll
+        for (int u = 0; u < U; ++u) { xh[u][nb] = ph[u * 64]; xl[u][nb] = pl[u * 64]; }
+    }
+    for (int i = 0; i < nt; ++i) {
+        const uint4 *wp = a.w + ((int64_t)(tb0 + i) * KS + kw0) * 64 + lane;
+        uint4 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) w[u] = wp[u * 64];
+        // keep all U loads in flight: without this the scheduler interleaves load / wait / multiply
+        // through one register quad and the wave has a single KiB outstanding
+        __builtin_amdgcn_sched_barrier(0);
+        floatx4_t acc_h[NB], acc_l[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) { acc_h[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; acc_l[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                acc_h[nb] = mfma16(w[u], xh[u][nb], acc_h[nb]);
+                acc_l[nb] = mfma16(w[u], xl[u][nb], acc_l[nb]);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float4 v = make_float4(acc_h[nb][0] + acc_l[nb][0], acc_h[nb][1] + acc_l[nb][1], acc_h[nb][2] + acc_l[nb][2],
+                                   acc_h[nb][3] + acc_l[nb][3]);
+            float4 *slot = &red[((i * WAVES + wave) * NB + nb) * 64 + lane];    // this wave's own slot
+            if (!first) { const float4 o = *slot; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+            *slot = v;
+        }
+    }
+}
+
 template <int NB, int UK, int TB, int kXsWaves, int MODE>
 __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 {
@@ -125,75 +174,49 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int KS = a.KS, Rg = a.Rg;
     const int rg = blockIdx.x;
-    const int per = (KS + kXsWaves - 1) / kXsWaves;                  // k-steps owned by a wave
-    const int kown0 = wave * per, kown1 = min(KS, kown0 + per);
+    // the wave's contiguous share of the k-steps (shares differ by at most one step)
+    const int kown0 = (int)((int64_t)wave * KS / kXsWaves), kown1 = (int)((int64_t)(wave + 1) * KS / kXsWaves);
     const int rt0 = (int)((int64_t)rg * a.n_tiles / Rg), rt1 = (int)((int64_t)(rg + 1) * a.n_tiles / Rg);
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
     for (int tb0 = rt0; tb0 < rt1; tb0 += TB) {
         const int nt = min(TB, rt1 - tb0);
-        for (int kw0 = kown0, pass = 0; kw0 < kown1; kw0 += UK, ++pass) {
-            const int kw1 = min(kown1, kw0 + UK);
-            // Loads are unconditional 16-byte vectors at constant offsets from one base: the
-            // window of UK k-steps starts at kbase (pulled back so it stays inside the matrix,
-            // KS >= UK); steps outside [kw0, kw1) are nulled through the weights.  Batch rows past
-            // the live batch re-read the last live row: their output columns are never stored, and
-            // a matrix-core output column depends on its own activation column only.
-            const int kbase = max(0, min(kw0, KS - UK));
-            bool kvalid[UK];
-#pragma unroll
-            for (int u = 0; u < UK; ++u) kvalid[u] = (kbase + u >= kw0) && (kbase + u < kw1);
-            uint4 xh[UK][NB], xl[UK][NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int rsel = min(lane & 15, a.B - 1 - nb * 16);
-                {
-                    const uint4 *ph = a.xhi + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
-                    const uint4 *pl = a.xlo + (nb * KS + kbase) * 64 + (lane >> 4) * 16 + rsel;
-#pragma unroll
-                    for (int u = 0; u < UK; ++u) { xh[u][nb] = ph[u * 64]; xl[u][nb] = pl[u * 64]; }
-                }
+        // passes of 8 k-steps and one exact remainder pass cover the share: no block of W is read twice
+        for (int k = kown0; k < kown1;) {
+            const int rem = kown1 - k;
+            const bool first = k == kown0;
+            if (rem >= 8) { xs_pass<NB, 8, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); k += 8; continue; }
+            switch (rem) {
+            case 7: xs_pass<NB, 7, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            case 6: xs_pass<NB, 6, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            case 5: xs_pass<NB, 5, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            case 4: xs_pass<NB, 4, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            case 3: xs_pass<NB, 3, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            case 2: xs_pass<NB, 2, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
+            default: xs_pass<NB, 1, kXsWaves>(a, lane, wave, k, tb0, nt, first, red); break;
             }
-            for (int i = 0; i < nt; ++i) {
-                const uint4 *wp = a.w + ((int64_t)(tb0 + i) * KS + kbase) * 64 + lane;
-                uint4 w[UK];
-#pragma unroll
-                for (int u = 0; u < UK; ++u) w[u] = wp[u * 64];
-#pragma unroll
-                for (int u = 0; u < UK; ++u) if (!kvalid[u]) w[u] = zero4;
-                floatx4_t acc_h[NB], acc_l[NB];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) { acc_h[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; acc_l[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-                for (int u = 0; u < UK; ++u) {
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        acc_h[nb] = mfma16(w[u], xh[u][nb], acc_h[nb]);
-                        acc_l[nb] = mfma16(w[u], xl[u][nb], acc_l[nb]);
-                    }
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    float4 v = make_float4(acc_h[nb][0] + acc_l[nb][0], acc_h[nb][1] + acc_l[nb][1],
-                                           acc_h[nb][2] + acc_l[nb][2], acc_h[nb][3] + acc_l[nb][3]);
-                    float4 *slot = &red[((i * kXsWaves + wave) * NB + nb) * 64 + lane];    // this wave's own slot
-                    if (pass > 0) { const float4 o = *slot; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
-                    *slot = v;
-                }
-            }
+            k = kown1;
         }
         __syncthreads();
         if (wave < nt) {
             // D tile layout: lane l holds rows (l/16)*4 .. +3 of column l%16 = 4 consecutive
-            // output features of one batch row.  Waves that own no k-steps left no partial.
+            // output features of one batch row.  Waves with an empty share left no partial.
             const int rt = tb0 + wave;
-            const int nw = min(kXsWaves, (KS + per - 1) / per);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                float4 v = red[((wave * kXsWaves + 0) * NB + nb) * 64 + lane];
-                for (int ww = 1; ww < nw; ++ww) {
-                    const float4 t = red[((wave * kXsWaves + ww) * NB + nb) * 64 + lane];
-                    v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (KS >= kXsWaves) {                                      // every wave owns k-steps
+                    v = red[(wave * kXsWaves * NB + nb) * 64 + lane];
+#pragma unroll
+                    for (int ww = 1; ww < kXsWaves; ++ww) {
+                        const float4 t = red[((wave * kXsWaves + ww) * NB + nb) * 64 + lane];
+                        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+                    }
+                } else {
+                    for (int ww = 0; ww < kXsWaves; ++ww) {
+                        if ((ww + 1) * KS / kXsWaves == ww * KS / kXsWaves) continue;   // empty share: no partial
+                        const float4 t = red[((wave * kXsWaves + ww) * NB + nb) * 64 + lane];
+                        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+                    }
                 }
                 gemm_epilogue<MODE>(a, rt, lane >> 4, nb * 16 + (lane & 15), v);
             }
@@ -575,7 +598,7 @@ void gemm_set_compute_units(int n) { if (n > 0) g_target_wgs = n; }
 GemmPlan gemm_plan(int n_tiles, int KS, int B)
 {
     GemmPlan p{1, 1, 4, 1};
-    if (B <= 32 && KS >= 16) {
+    if (B <= 32) {
         p.Kb = 1;                                              // a workgroup walks all of K itself
         p.Rg = n_tiles < g_target_wgs ? n_tiles : g_target_wgs;
     } else if (KS >= kXlP) {
@@ -605,8 +628,8 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     a.Kb = p.Kb; a.Rg = p.Rg;
     if (a.Kb > 1 && a.part == nullptr) return hipErrorInvalidValue;
     // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
-    if (a.B <= 16 && a.KS >= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
-    if (a.B <= 32 && a.KS >= 16) return launch_xs<2, 8, 8, 8>(a, mode, s);
+    if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
+    if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
     hipError_t e;
     if (a.KS >= kXlP) e = p.MT == 1 ? launch_xl<1>(a, mode, s) : p.MT == 2 ? launch_xl<2>(a, mode, s) : launch_xl<4>(a, mode, s);
     else e = launch_tiled<4, 1>(a, mode, s);
