@@ -56,6 +56,23 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         const int cnt = min(n - t0, C);
         const int32_t *pt = a.page_table + (int64_t)b * a.max_pages;
         const int64_t head_off = (int64_t)h * P * D + seg * 8;
+        // UR token rows per thread, requested together: page indices first (unconditional, clamped to
+        // the chunk's last token), then the rows.  Conditional loads would serialise into
+        // load / wait pairs and leave one row in flight per thread.
+        auto load_rows = [&](const uint16_t *base, int r0, uint4 (&rows)[UR], bool (&okk)[UR]) {
+            int page[UR], tc[UR];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const int tl = r0 + u * TPR + ts;
+                okk[u] = tl < cnt;
+                tc[u] = t0 + min(tl, cnt - 1);
+                page[u] = pt[tc[u] / P];
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u)
+                rows[u] = *reinterpret_cast<const uint4 *>(base + page[u] * page_elems + head_off + (int64_t)(tc[u] % P) * D);
+            __builtin_amdgcn_sched_barrier(0);
+        };
 
         float q[G][8];
 #pragma unroll
@@ -70,32 +87,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         // The first batch of V rows is requested together with the K rows: a short chunk then
         // pays one memory latency instead of two.
         uint4 vfirst[UR];
-#pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            const int tl = u * TPR + ts;
-            vfirst[u] = make_uint4(0, 0, 0, 0);
-            if (tl < cnt) {
-                const int t = t0 + tl;
-                const int page = pt[t / P];
-                vfirst[u] = *reinterpret_cast<const uint4 *>(vbase + page * page_elems + head_off + (int64_t)(t % P) * D);
-            }
-        }
+        bool okv[UR];
+        load_rows(vbase, 0, vfirst, okv);
 
         // ---- scores of the chunk ----
         for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
             uint4 kv[UR];
             bool ok[UR];
-#pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const int tl = r0 + u * TPR + ts;
-                ok[u] = tl < cnt;
-                kv[u] = make_uint4(0, 0, 0, 0);
-                if (ok[u]) {
-                    const int t = t0 + tl;
-                    const int page = pt[t / P];
-                    kv[u] = *reinterpret_cast<const uint4 *>(kbase + page * page_elems + head_off + (int64_t)(t % P) * D);
-                }
-            }
+            load_rows(kbase, r0, kv, ok);
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
                 const float k0 = bf16lo(kv[u].x), k1 = bf16hi(kv[u].x), k2 = bf16lo(kv[u].y), k3 = bf16hi(kv[u].y);
@@ -139,16 +138,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
             uint4 kv[UR];
             bool ok[UR];
+            if (r0 == 0) {
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const int tl = r0 + u * TPR + ts;
-                ok[u] = tl < cnt;
-                kv[u] = vfirst[u];
-                if (ok[u] && r0 > 0) {
-                    const int t = t0 + tl;
-                    const int page = pt[t / P];
-                    kv[u] = *reinterpret_cast<const uint4 *>(vbase + page * page_elems + head_off + (int64_t)(t % P) * D);
-                }
+                for (int u = 0; u < UR; ++u) { kv[u] = vfirst[u]; ok[u] = okv[u]; }
+            } else {
+                load_rows(vbase, r0, kv, ok);
             }
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
