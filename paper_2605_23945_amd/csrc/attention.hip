@@ -200,18 +200,30 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a)
     const int ce0 = a.chunk_start[b], nch = a.chunk_start[b + 1] - ce0;
     const int KS = a.hq * D / 32;
     float M = -INFINITY, den = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int c = cl; c < nch; c += CL) {
-        const float *mlp = a.part_ml + ((int64_t)(ce0 + c) * a.hq + head) * 2;
-        const float m = mlp[0], l = mlp[1];
-        const float *ap = a.part_acc + ((int64_t)(ce0 + c) * a.hq + head) * D + seg * 8;
-        const float4 p0 = *reinterpret_cast<const float4 *>(ap);
-        const float4 p1 = *reinterpret_cast<const float4 *>(ap + 4);
-        const float Mn = fmaxf(M, m);
-        const float so = expf(M - Mn), sn = expf(m - Mn);       // M = -inf on the first chunk: so = 0
-        den = den * so + l * sn;
-        o[0] = o[0] * so + p0.x * sn; o[1] = o[1] * so + p0.y * sn; o[2] = o[2] * so + p0.z * sn; o[3] = o[3] * so + p0.w * sn;
-        o[4] = o[4] * so + p1.x * sn; o[5] = o[5] * so + p1.y * sn; o[6] = o[6] * so + p1.z * sn; o[7] = o[7] * so + p1.w * sn;
-        M = Mn;
+    // four chunks' partials are requested together, then folded in chunk order
+    for (int c0 = cl; c0 < nch; c0 += 4 * CL) {
+        float m[4], l[4];
+        float4 p0[4], p1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = min(c0 + i * CL, nch - 1);               // clamped: always a valid chunk
+            const float2 mlv = *reinterpret_cast<const float2 *>(a.part_ml + ((int64_t)(ce0 + c) * a.hq + head) * 2);
+            m[i] = mlv.x; l[i] = mlv.y;
+            const float *ap = a.part_acc + ((int64_t)(ce0 + c) * a.hq + head) * D + seg * 8;
+            p0[i] = *reinterpret_cast<const float4 *>(ap);
+            p1[i] = *reinterpret_cast<const float4 *>(ap + 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c0 + i * CL >= nch) break;
+            const float Mn = fmaxf(M, m[i]);
+            const float so = expf(M - Mn), sn = expf(m[i] - Mn);       // M = -inf on the first chunk: so = 0
+            den = den * so + l[i] * sn;
+            o[0] = o[0] * so + p0[i].x * sn; o[1] = o[1] * so + p0[i].y * sn; o[2] = o[2] * so + p0[i].z * sn; o[3] = o[3] * so + p0[i].w * sn;
+            o[4] = o[4] * so + p1[i].x * sn; o[5] = o[5] * so + p1[i].y * sn; o[6] = o[6] * so + p1[i].z * sn; o[7] = o[7] * so + p1[i].w * sn;
+            M = Mn;
+        }
     }
 #pragma unroll
     for (int off = 32; off >= LPT; off >>= 1) {
