@@ -63,7 +63,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_fi
            "pat_kv_write", "pat_kv_read", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_rmsnorm_pack", "pat_op_argmax"]
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax"]
 
 _lib = None
 
@@ -106,6 +106,8 @@ def load_library() -> C.CDLL:
     lib.pat_op_gemm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
     lib.pat_op_gemm_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.pat_op_gemm_scratch_bytes.restype = C.c_int64
+    lib.pat_op_gemm_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+    lib.pat_op_gemm_plan.restype = C.c_int
     lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     _lib = lib

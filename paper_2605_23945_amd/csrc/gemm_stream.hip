@@ -19,6 +19,8 @@
 // The tiled kernel can also split K across workgroups; the slice partials go to a
 // scratch tensor and gemm_reduce_kernel adds them in slice order, so results never
 // depend on timing.
+#include <algorithm>
+#include <cstdlib>
 #include "pat_dev.h"
 #include "pat_kernels.h"
 
@@ -28,6 +30,24 @@ namespace {
 
 
 __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+}
+
+// Native vector flavour of a 16-byte fragment.  Values that are loaded in one loop iteration and
+// used in a later one are held in this type: assignments of the runtime's uint4 class can be
+// lowered to memcpy between address spaces, which pins the variable in scratch memory.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t ld16(const uint4 *p) { return *reinterpret_cast<const u32x4_t *>(p); }
+__device__ __forceinline__ void st16(uint4 *p, u32x4_t v) { *reinterpret_cast<u32x4_t *>(p) = v; }
+__device__ __forceinline__ floatx4_t mfma16(u32x4_t a, uint4 b, floatx4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+}
+
+__device__ __forceinline__ floatx4_t mfma16(u32x4_t a, u32x4_t b, floatx4_t c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
                                                    0, 0, 0);
@@ -431,6 +451,158 @@ __global__ __launch_bounds__(kXlWaves * 64) void gemm_xl_kernel(GemmArgs a)
     }
 }
 
+// ---- live batch 33..256: full-batch tiles ---------------------------------------------
+// The weights are streamed ONCE for the whole live batch.  A workgroup of NW waves owns a
+// contiguous range of row tiles x ALL batch tiles x a K slice and walks its rows in chunks of
+// WR * RA tiles.  The waves form a WR x WC grid: a wave keeps RA row tiles x RBT batch tiles of
+// accumulators, takes its weight fragments straight from HBM and the batch tiles' split-bf16
+// fragments from LDS, where one k-step of ALL batch tiles is staged per barrier.
+// Rates per stage that shaped it (CDNA: 128 B/clk of LDS and 64 B/clk of vector memory per compute
+// unit, 16 clk per 16x16x32 matrix instruction and SIMD): a fragment read from LDS must feed at
+// least 4 matrix instructions (RA = 4, both halves), and a wave must request all of a stage's
+// fragments before its first matrix instruction, or the LDS latency is paid once per pair.
+// A stage is requested from memory D - 1 stages before it is used and waits in registers (a ring
+// of D register sets, written out so that every slot is a fixed set of registers).
+// Every workgroup re-reads the activations of its K slice once per chunk, out of L2 or the
+// memory-side cache; with 256 workgroups that traffic, not HBM and not the matrix cores, is what
+// bounds the kernel (about 9 TB/s delivered in all), hence chunks of 16 row tiles.
+template <int NW, int WC, int RBT, int RA, int D, int MODE>
+__global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
+{
+    constexpr int WR = NW / WC, NBT = WC * RBT, CH = WR * RA;
+    constexpr int NV = 2 * NBT * 64;                 // vectors per stage: [2 (hi, lo)][NBT][64]
+    constexpr int VPT = NV / (NW * 64);
+    static_assert(NV % (NW * 64) == 0 && VPT <= 4, "a stage is one to four vectors per thread");
+    static_assert(D == 2 || D == 4, "ring of two or four stages");
+    extern __shared__ uint4 xs[];                    // two stages
+    // the wave index as a scalar: what derives from it (row tiles, fragment bases) stays in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave / WC, wc = wave - wr * WC;
+    const int KS = a.KS, kb = blockIdx.y;
+    const int ks0 = (int)((int64_t)kb * KS / a.Kb), ks1 = (int)((int64_t)(kb + 1) * KS / a.Kb);
+    const int rt0 = (int)((int64_t)blockIdx.x * a.n_tiles / a.Rg), rt1 = (int)((int64_t)(blockIdx.x + 1) * a.n_tiles / a.Rg);
+    const u32x4_t zero_v = {0u, 0u, 0u, 0u};
+    const int n_stage = ks1 - ks0;
+
+    // This thread's vector i of a stage is the same (half, batch tile, lane) for every k-step: a
+    // wave-uniform base (unit i * NW + wave of the stage) plus a 32-bit lane offset.  Batch rows past
+    // the live batch re-read the last live row (their columns are never stored).
+    auto xsrc = [&](int i) -> const uint4 * {
+        const int unit = i * NW + wave, bt = unit % NBT, half = unit / NBT;
+        const int bsel = min(bt * 16 + (lane & 15), a.B - 1);
+        const uint32_t off = (uint32_t)(bsel >> 4) * (uint32_t)(KS * 64) + (uint32_t)((lane >> 4) * 16 + (bsel & 15));
+        return (half ? a.xlo : a.xhi) + off;
+    };
+
+    for (int c0 = rt0; c0 < rt1; c0 += CH) {
+        const int t0 = c0 + wr * RA;
+        const int n_live = min(max(rt1 - t0, 0), RA);          // row tiles of this wave inside the range
+        const uint4 *wsrc[RA];
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra) wsrc[ra] = a.w + (int64_t)min(t0 + ra, rt1 - 1) * KS * 64;
+        floatx4_t acc[RA][RBT];
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra)
+#pragma unroll
+            for (int rb = 0; rb < RBT; ++rb) acc[ra][rb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+        // All loads are unconditional, from clamped (always valid) addresses: k-steps past the slice
+        // re-read its last one and are nulled through the weights, as are row tiles past the range.
+        struct XStage { u32x4_t v0, v1, v2, v3; };
+        XStage xr0, xr1, xr2, xr3;
+        u32x4_t wq0[RA], wq1[RA], wq2[RA], wq3[RA];
+#define PAT_XB_FETCH(stage_, xr_, wq_)                                                           \
+    {                                                                                            \
+        const int ks_ = ks0 + (stage_);                                                          \
+        const int ksc_ = min(ks_, ks1 - 1) * 64;                                                 \
+        xr_.v0 = ld16(xsrc(0) + ksc_);                                                           \
+        if (VPT > 1) xr_.v1 = ld16(xsrc(1) + ksc_);                                              \
+        if (VPT > 2) xr_.v2 = ld16(xsrc(2) + ksc_);                                              \
+        if (VPT > 3) xr_.v3 = ld16(xsrc(3) + ksc_);                                              \
+        _Pragma("unroll") for (int ra = 0; ra < RA; ++ra) {                                      \
+            const u32x4_t v_ = ld16(wsrc[ra] + ksc_ + lane);                                          \
+            wq_[ra] = (ks_ < ks1 && ra < n_live) ? v_ : zero_v;                                  \
+        }                                                                                        \
+    }
+#define PAT_XB_TO_LDS(dst_, xr_)                                                                 \
+    {                                                                                            \
+        st16(dst_ + tid, xr_.v0);                                                                \
+        if (VPT > 1) st16(dst_ + 1 * (NW * 64) + tid, xr_.v1);                                   \
+        if (VPT > 2) st16(dst_ + 2 * (NW * 64) + tid, xr_.v2);                                   \
+        if (VPT > 3) st16(dst_ + 3 * (NW * 64) + tid, xr_.v3);                                   \
+    }
+// multiply the stage in LDS buffer u_ & 1: its fragments are read in groups of G (high halves first,
+// then low halves), the next group requested before the current one is multiplied
+#define PAT_XB_MUL(u_, wcur_)                                                                    \
+    if (n_live > 0) {                                                                            \
+        constexpr int G = RA * RBT >= 32 ? 2 : (RBT < 4 ? RBT : 4), NG = 2 * RBT / G;           \
+        const uint4 *buf = xs + ((u_) & 1) * NV + (wc * RBT) * 64 + lane;                        \
+        u32x4_t f[2][G];                                                                         \
+        _Pragma("unroll") for (int j = 0; j < G; ++j) f[0][j] = ld16(buf + j * 64);              \
+        _Pragma("unroll") for (int g = 0; g < NG; ++g) {                                         \
+            if (g + 1 < NG) {                                                                    \
+                const int half = (g + 1) / (RBT / G), rb0 = ((g + 1) % (RBT / G)) * G;           \
+                _Pragma("unroll") for (int j = 0; j < G; ++j)                                    \
+                    f[(g + 1) & 1][j] = ld16(buf + (half * NBT + rb0 + j) * 64);                 \
+            }                                                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                   \
+            const int rbc = (g % (RBT / G)) * G;                                                 \
+            _Pragma("unroll") for (int j = 0; j < G; ++j)                                        \
+                _Pragma("unroll") for (int ra = 0; ra < RA; ++ra)                                \
+                    acc[ra][rbc + j] = mfma16(wcur_[ra], f[g & 1][j], acc[ra][rbc + j]);         \
+        }                                                                                        \
+    }
+// stage t: request stage t + D - 1 into the ring slot freed last, multiply stage t out of LDS buffer
+// t & 1, then move stage t + 1 into the other buffer
+#define PAT_XB_STAGE(u_, ahead_, xfetch_, wfetch_, wcur_, xnext_)                                \
+    {                                                                                            \
+        PAT_XB_FETCH(tb + (u_) + (ahead_), xfetch_, wfetch_)                                     \
+        PAT_XB_MUL(u_, wcur_)                                                                    \
+        uint4 *nxt = xs + (((u_) + 1) & 1) * NV;                                                 \
+        PAT_XB_TO_LDS(nxt, xnext_)                                                               \
+        __syncthreads();                                                                         \
+    }
+        // rounds of D stages; stages past the slice, when D does not divide its length, multiply
+        // nulled weights
+        PAT_XB_FETCH(0, xr0, wq0)
+        if (D == 4) {
+            PAT_XB_FETCH(1, xr1, wq1)
+            PAT_XB_FETCH(2, xr2, wq2)
+            PAT_XB_TO_LDS(xs, xr0)
+            __syncthreads();
+            for (int tb = 0; tb < n_stage; tb += 4) {
+                PAT_XB_STAGE(0, 3, xr3, wq3, wq0, xr1)
+                PAT_XB_STAGE(1, 3, xr0, wq0, wq1, xr2)
+                PAT_XB_STAGE(2, 3, xr1, wq1, wq2, xr3)
+                PAT_XB_STAGE(3, 3, xr2, wq2, wq3, xr0)
+            }
+        } else {
+            PAT_XB_TO_LDS(xs, xr0)
+            __syncthreads();
+            for (int tb = 0; tb < n_stage; tb += 2) {
+                PAT_XB_STAGE(0, 1, xr1, wq1, wq0, xr1)
+                PAT_XB_STAGE(1, 1, xr0, wq0, wq1, xr0)
+            }
+        }
+#undef PAT_XB_MUL
+#undef PAT_XB_STAGE
+#undef PAT_XB_TO_LDS
+#undef PAT_XB_FETCH
+
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra) {
+            if (ra >= n_live) continue;
+#pragma unroll
+            for (int rb = 0; rb < RBT; ++rb) {
+                const float4 v = make_float4(acc[ra][rb][0], acc[ra][rb][1], acc[ra][rb][2], acc[ra][rb][3]);
+                const int b = (wc * RBT + rb) * 16 + (lane & 15);
+                if (a.Kb == 1) gemm_epilogue<MODE>(a, t0 + ra, lane >> 4, b, v);
+                else store_partial(a, kb, t0 + ra, lane >> 4, b, v);
+            }
+        }
+    }
+}
+
 // Sum of the K-slice partials in slice order, then the epilogue.  One thread per
 // (batch row, 4 consecutive output features).
 template <int MODE>
@@ -590,20 +762,72 @@ hipError_t launch_xl(const GemmArgs &a, int mode, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int NW, int WC, int RBT, int RA, int D>
+hipError_t launch_xb(const GemmArgs &a, int mode, hipStream_t s)
+{
+    const dim3 grid(a.Rg, a.Kb);
+    constexpr size_t lds = (size_t)2 * 2 * WC * RBT * 64 * sizeof(uint4);
+    switch (mode) {
+    case kGemmStore: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmStore><<<grid, NW * 64, lds, s>>>(a); break;
+    case kGemmAccum: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmAccum><<<grid, NW * 64, lds, s>>>(a); break;
+    case kGemmQKV: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmQKV><<<grid, NW * 64, lds, s>>>(a); break;
+    default: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmSwiGLU><<<grid, NW * 64, lds, s>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 static int g_target_wgs = 256;   // one resident workgroup per compute unit
 void gemm_set_compute_units(int n) { if (n > 0) g_target_wgs = n; }
 
+// Shape of the full-batch kernel for a live batch: batch tiles held, wave grid, k-steps per stage.
+struct XbShape { int NBT, NW, WC, RBT, RA; };
+static XbShape xb_shape(int B)
+{
+    if (B <= 64) return {4, 8, 1, 4, 2};
+    if (B <= 128) return {8, 8, 2, 4, 4};
+    return {16, 8, 2, 8, 4};
+}
+
+// Row ranges and K slices of the full-batch kernel.  Measured on MI355X (7B shapes, live batch 64 to
+// 256): the time of a launch follows the k-steps a workgroup walks, so the chip is covered with about
+// one workgroup per compute unit, each holding ONE chunk of at most 16 row tiles (every further
+// chunk re-reads the activations), and K is split only as far as that needs (each slice costs a
+// round trip of partial sums).
+static void plan_xb(int n_tiles, int KS, int B, GemmPlan &p)
+{
+    const XbShape sh = xb_shape(B);
+    const int CH = (sh.NW / sh.WC) * sh.RA;
+    const int chunks = (n_tiles + CH - 1) / CH;
+    int kb = std::max(1, std::min(8, g_target_wgs / chunks));
+    while (kb > 1 && KS / kb < 8) --kb;                         // at least 8 k-steps per slice
+    const int rg = std::max(1, std::min(n_tiles, g_target_wgs / kb));   // more than 16 tiles each: several chunks
+    p.Kb = kb; p.Rg = rg; p.NB = sh.NBT; p.MT = sh.NW;
+}
+
+// tuning knob: PAT_GEMM_XB_MIN_BATCH in the environment moves the switch-over batch
+static int xb_min_batch_default()
+{
+    const char *e = getenv("PAT_GEMM_XB_MIN_BATCH");
+    return e && atoi(e) > 32 ? atoi(e) : 33;
+}
+static int g_xb_min_batch = xb_min_batch_default();
+void gemm_set_xb_min_batch(int b) { g_xb_min_batch = b; }
+
 GemmPlan gemm_plan(int n_tiles, int KS, int B)
 {
-    GemmPlan p{1, 1, 4, 1};
+    GemmPlan p{1, 1, 4, 1, kAlgoXs};
     if (B <= 32) {
         p.Kb = 1;                                              // a workgroup walks all of K itself
         p.Rg = n_tiles < g_target_wgs ? n_tiles : g_target_wgs;
+    } else if (B >= g_xb_min_batch && KS >= 16) {
+        p.algo = kAlgoXb;
+        plan_xb(n_tiles, KS, B, p);
     } else if (KS >= kXlP) {
         // batch groups of 64 rows; 16 / WS row tiles per workgroup; widen WS, then split K, until the
         // chip is covered (the partial sums of a narrow matrix are small)
+        p.algo = kAlgoXl;
         p.NB = kXlNB;
         const int bgroups = (B + 63) / 64;
         int ws = 1, kb = 1;
@@ -614,6 +838,7 @@ GemmPlan gemm_plan(int n_tiles, int KS, int B)
         p.Kb = kb;
         p.Rg = wgs();
     } else {
+        p.algo = kAlgoTiled;
         p.NB = 4; p.MT = 1; p.Kb = 1; p.Rg = 1;               // tiny K: the generic tiled kernel
     }
     return p;
@@ -631,7 +856,9 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
     if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
     hipError_t e;
-    if (a.KS >= kXlP) e = p.MT == 1 ? launch_xl<1>(a, mode, s) : p.MT == 2 ? launch_xl<2>(a, mode, s) : launch_xl<4>(a, mode, s);
+    if (p.algo == kAlgoXb)
+        e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s) : p.NB == 8 ? launch_xb<8, 2, 4, 4, 4>(a, mode, s) : launch_xb<8, 2, 8, 4, 2>(a, mode, s);
+    else if (p.algo == kAlgoXl) e = p.MT == 1 ? launch_xl<1>(a, mode, s) : p.MT == 2 ? launch_xl<2>(a, mode, s) : launch_xl<4>(a, mode, s);
     else e = launch_tiled<4, 1>(a, mode, s);
     if (e != hipSuccess || a.Kb == 1) return e;
     const int64_t n = (int64_t)a.B * a.n_tiles * 4;

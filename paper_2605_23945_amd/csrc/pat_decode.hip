@@ -148,8 +148,7 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
                                 {s.H / 16, s.F / 32}, {s.Vs / 16, s.H / 32}};
         int64_t need = 0;
         for (auto &mt : mats)
-            for (int B : {16, 32, 64, 128, 256}) {
-                const int b = std::min(B, MB);
+            for (int b = 33; b <= std::min(256, MB); ++b) {
                 const int kb = gemm_plan(mt[0], mt[1], b).Kb;
                 if (kb > 1) need = std::max(need, (int64_t)kb * b * mt[0] * 16 * 4);
             }
@@ -714,6 +713,14 @@ int64_t pat_op_gemm_scratch_bytes(int32_t n, int32_t k, int32_t b)
     if (n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256) return -1;
     const int kb = gemm_plan(cdiv(n, 16), k / 32, b).Kb;
     return kb > 1 ? (int64_t)kb * b * cdiv(n, 16) * 16 * 4 : 0;
+}
+
+int pat_op_gemm_plan(int32_t n, int32_t k, int32_t b, int32_t plan[4])
+{
+    if (!plan || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256) return PAT_EINVAL;
+    const GemmPlan p = gemm_plan(cdiv(n, 16), k / 32, b);
+    plan[0] = p.algo; plan[1] = p.Kb; plan[2] = p.Rg; plan[3] = p.algo == kAlgoXs ? (b <= 16 ? 1 : 2) : p.NB;
+    return PAT_OK;
 }
 
 int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b, float *y,

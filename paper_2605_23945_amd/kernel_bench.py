@@ -11,6 +11,7 @@ counters calibrate the unit of the projection kernels' counters.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import os
 import sys
 
@@ -83,8 +84,10 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             us = e0.elapsed_time(e1) * 1e3 / args.iters
+            plan = (ctypes.c_int32 * 4)()
+            lib.pat_op_gemm_plan(n, k, b, plan)
             print(f"{name:8s} N={n:6d} K={k:6d} B={b:4d}  {us:8.1f} us  weights {n * k * 2} B  {n * k * 2 / us / 1e6:6.2f} TB/s  "
-                  f"{n * k * 2 / us / 1e6 / 8.0:6.1%} of 8 TB/s", flush=True)
+                  f"{n * k * 2 / us / 1e6 / 8.0:6.1%} of 8 TB/s  plan(kernel,Kb,Rg,tiles)={list(plan)}", flush=True)
 
 
 if __name__ == "__main__":

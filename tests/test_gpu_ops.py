@@ -57,7 +57,9 @@ def test_weight_packing_and_mfma_layout_exact(pat):
 
 @pytest.mark.parametrize("n,k,b", [(256, 1024, 1), (256, 1024, 5), (1040, 352, 16), (512, 2752, 17), (96, 4096, 33),
                                    (64, 256, 100), (48, 64, 256), (4096, 4096, 8), (16, 32, 3),
-                                   (4096, 1024, 200), (528, 2752, 130), (1024, 4096, 40), (256, 8192, 30)])
+                                   (4096, 1024, 200), (528, 2752, 130), (1024, 4096, 40), (256, 8192, 30),
+                                   (4096, 4096, 256), (2048, 11008, 96), (8192, 512, 192), (16384, 1024, 255),
+                                   (34000, 512, 250), (4112, 1024, 65), (22016, 1024, 129)])
 def test_gemm_store_and_accumulate_vs_oracle(pat, orc, n, k, b):
     w, x = _w(n, k, 2 + n + k), _x(b, k, n + b)
     wp = pat.pat_op_pack_weight(w.to(DEV))
@@ -76,7 +78,8 @@ def test_gemm_store_and_accumulate_vs_oracle(pat, orc, n, k, b):
         assert np.max(np.abs(y1[r].cpu().double().numpy() - (ref + y0[r].double().numpy()))) <= 1e-4 * scale + 1e-6
 
 
-@pytest.mark.parametrize("f,k,b", [(64, 256, 3), (352, 512, 16), (1024, 256, 40), (512, 2048, 70), (64, 4096, 9)])
+@pytest.mark.parametrize("f,k,b", [(64, 256, 3), (352, 512, 16), (1024, 256, 40), (512, 2048, 70), (64, 4096, 9),
+                                   (2752, 1024, 256), (1376, 4096, 150)])
 def test_gemm_swiglu_epilogue_vs_oracle(pat, orc, f, k, b):
     wg, wu, x = _w(f, k, 11, 0.05), _w(f, k, 12, 0.05), _x(b, k, 5)
     wp = pat.pat_op_pack_weight(wg.to(DEV), wu.to(DEV))

@@ -304,6 +304,18 @@ def test_7b_tp4_shard_shape_two_layers_sampled_rows():
     _sampled_rows_parity(shard, 70, (100, 600), [0, 31, 32, 69], steps=2)     # 70 rows: five batch tiles, two batch groups
 
 
+def test_7b_shape_two_layers_batch_200_full_batch_projections():
+    """Live batch 200 (13 batch tiles, the last one ragged): the projections that hold the whole batch."""
+    shard = pi.CONFIGS["7b_tp1"]["shard"].with_layers(2)
+    _sampled_rows_parity(shard, 200, (64, 300), [0, 63, 64, 127, 128, 191, 192, 199], steps=2)
+
+
+def test_13b_tp2_shard_batch_130_full_batch_projections():
+    """Live batch 130 (nine batch tiles -> the 12-tile shape) on the hidden-5120 shard."""
+    shard = pi.CONFIGS["13b_tp2"]["shard"].with_layers(2)
+    _sampled_rows_parity(shard, 130, (64, 200), [0, 64, 128, 129], steps=1)
+
+
 def test_13b_tp2_shard_shape_two_layers_sampled_rows():
     """Configuration 4's shard: hidden 5120, 20 of 40 heads, FFN slice 6912, vocabulary slice 16000."""
     shard = pi.CONFIGS["13b_tp2"]["shard"].with_layers(2)
