@@ -201,8 +201,8 @@ int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, 
  * workgroups; they are added in slice order. */
 int64_t pat_op_gemm_scratch_bytes(int32_t n, int32_t k, int32_t b);
 /* How pat_op_gemm / the step cut an [n, k] projection at live batch b (diagnostics, host only):
- * plan[0] kernel (0 small-batch streaming, 1 batch-grouped, 2 generic tiled, 3 full-batch),
- * plan[1] K slices across workgroups, plan[2] row ranges, plan[3] batch tiles held per workgroup.
+ * plan[0] kernel (0 small-batch streaming, live batch <= 32; 3 full-batch), plan[1] K slices across
+ * workgroups, plan[2] row ranges, plan[3] batch tiles held per workgroup.
  * Returns PAT_EINVAL for shapes pat_op_gemm rejects. */
 int pat_op_gemm_plan(int32_t n, int32_t k, int32_t b, int32_t plan[4]);
 int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b,

@@ -13,10 +13,10 @@
 //  - gemm_xs_kernel (live batch <= 32): activation-stationary; each wave keeps its
 //    K slice of the activations in registers and streams row tiles past it
 //    (wave-level split-K, partial tiles summed through LDS in wave order).
-//  - gemm_tiled_kernel (live batch 33..256): the batch is a real dense dimension;
-//    a workgroup owns 64 or 128 weight rows x a batch group of 64 or 128 rows, stages
-//    the activations of two k-steps in LDS for its four waves.
-// The tiled kernel can also split K across workgroups; the slice partials go to a
+//  - gemm_xb_kernel (live batch 33..256): the batch is a real dense dimension; a
+//    workgroup owns up to 16 weight row tiles x ALL batch tiles x a K slice and
+//    stages the activations of one k-step at a time in LDS for its eight waves.
+// The full-batch kernel can split K across workgroups; the slice partials go to a
 // scratch tensor and gemm_reduce_kernel adds them in slice order, so results never
 // depend on timing.
 #include <algorithm>
@@ -242,212 +242,6 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
             }
         }
         if (tb0 + TB < rt1) __syncthreads();
-    }
-}
-
-// ---- live batch 33..256 -------------------------------------------------------------
-// The batch is a real dense dimension.  A workgroup of 4 waves owns (4 MT row tiles) x (a
-// batch group of NB tiles) x (a K slice); each wave keeps MT x NB accumulator tiles.  The
-// batch group's split-bf16 fragments of two k-steps are staged in LDS (double-buffered,
-// one barrier per stage) and shared by the four waves; weight fragments go straight from
-// HBM to registers, loaded one stage ahead.
-constexpr int kTileWaves = 4, kTileS = 2;
-
-template <int NB, int MT, int MODE>
-__global__ __launch_bounds__(kTileWaves * 64) void gemm_tiled_kernel(GemmArgs a)
-{
-    extern __shared__ uint4 xs[];     // [2 buffers][2 (hi, lo)][kTileS][NB][64]
-    constexpr int NV = 2 * kTileS * NB * 64;          // vectors per stage
-    constexpr int VPT = NV / (kTileWaves * 64);       // per thread
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int KS = a.KS, kb = blockIdx.z;
-    const int ks0 = (int)((int64_t)kb * KS / a.Kb), ks1 = (int)((int64_t)(kb + 1) * KS / a.Kb);
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    const int rt0 = (blockIdx.x * kTileWaves + wave) * MT;
-    const int bt0 = blockIdx.y * NB;
-
-    floatx4_t acc[MT][NB];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-
-    // stage vector v = ((half * S + s) * NB + nb) * 64 + ln.  All loads are unconditional, from
-    // clamped (always valid) addresses: batch rows past the live batch re-read the last live row
-    // (their columns are never stored), k-steps past the slice re-read its last one and are
-    // nulled through the weights.
-    auto fetch_x = [&](int ks, uint4 (&r)[VPT]) {
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = i * (kTileWaves * 64) + tid;
-            const int ln = v & 63, nb = (v >> 6) % NB, s = ((v >> 6) / NB) % kTileS, half = (v >> 6) / (NB * kTileS);
-            const int bsel = min((bt0 + nb) * 16 + (ln & 15), a.B - 1);
-            const uint4 *src = half ? a.xlo : a.xhi;
-            r[i] = src[((int64_t)(bsel >> 4) * KS + min(ks + s, ks1 - 1)) * 64 + (ln >> 4) * 16 + (bsel & 15)];
-        }
-    };
-    auto fetch_w = [&](int ks, uint4 (&w)[kTileS][MT]) {
-#pragma unroll
-        for (int s = 0; s < kTileS; ++s)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const bool ok = (ks + s < ks1) && (rt0 + mt < a.n_tiles);
-                const uint4 v = a.w[((int64_t)min(rt0 + mt, a.n_tiles - 1) * KS + min(ks + s, ks1 - 1)) * 64 + lane];
-                w[s][mt] = ok ? v : zero4;
-            }
-    };
-
-    const int n_stage = (ks1 - ks0 + kTileS - 1) / kTileS;
-    uint4 xr[VPT], wr[kTileS][MT], wc[kTileS][MT];
-    fetch_x(ks0, xr);
-    fetch_w(ks0, wc);
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) xs[i * (kTileWaves * 64) + tid] = xr[i];
-    __syncthreads();
-    for (int t = 0; t < n_stage; ++t) {
-        const bool more = t + 1 < n_stage;
-        if (more) { fetch_x(ks0 + (t + 1) * kTileS, xr); fetch_w(ks0 + (t + 1) * kTileS, wr); }
-        const uint4 *buf = xs + (t & 1) * NV;
-#pragma unroll
-        for (int s = 0; s < kTileS; ++s) {
-#pragma unroll
-            for (int nb = 0; nb < NB; nb += 2) {
-                const uint4 h0 = buf[((0 * kTileS + s) * NB + nb) * 64 + lane];
-                const uint4 h1 = buf[((0 * kTileS + s) * NB + nb + 1) * 64 + lane];
-                const uint4 l0 = buf[((1 * kTileS + s) * NB + nb) * 64 + lane];
-                const uint4 l1 = buf[((1 * kTileS + s) * NB + nb + 1) * 64 + lane];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[mt][nb] = mfma16(wc[s][mt], h0, acc[mt][nb]);
-                    acc[mt][nb + 1] = mfma16(wc[s][mt], h1, acc[mt][nb + 1]);
-                }
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[mt][nb] = mfma16(wc[s][mt], l0, acc[mt][nb]);
-                    acc[mt][nb + 1] = mfma16(wc[s][mt], l1, acc[mt][nb + 1]);
-                }
-            }
-        }
-        if (more) {
-            uint4 *nxt = xs + ((t + 1) & 1) * NV;
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) nxt[i * (kTileWaves * 64) + tid] = xr[i];
-#pragma unroll
-            for (int s = 0; s < kTileS; ++s)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) wc[s][mt] = wr[s][mt];
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        if (rt0 + mt >= a.n_tiles) continue;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const float4 v = make_float4(acc[mt][nb][0], acc[mt][nb][1], acc[mt][nb][2], acc[mt][nb][3]);
-            const int b = (bt0 + nb) * 16 + (lane & 15);
-            if (a.Kb == 1) gemm_epilogue<MODE>(a, rt0 + mt, lane >> 4, b, v);
-            else store_partial(a, kb, rt0 + mt, lane >> 4, b, v);
-        }
-    }
-}
-
-// ---- live batch 33..256, main kernel: activations stationary in LDS ---------------------
-// A workgroup of 16 waves owns (16 / WS row tiles) x (a batch group of 64 rows) x (a K slice)
-// and walks the slice in passes of P k-steps.  Per pass the batch group's split-bf16
-// fragments are staged once in LDS (128 KiB) and every wave streams its P / WS weight
-// blocks of the pass from HBM against them; WS waves share a row tile and split the pass,
-// their partial tiles meet in LDS at the end and are summed in wave order.
-constexpr int kXlWaves = 16, kXlNB = 4, kXlP = 16;
-
-template <int WS, int MODE>
-__global__ __launch_bounds__(kXlWaves * 64) void gemm_xl_kernel(GemmArgs a)
-{
-    constexpr int NB = kXlNB, P = kXlP, PW = P / WS, R = kXlWaves / WS;
-    constexpr int NV = 2 * P * NB * 64, VPT = NV / (kXlWaves * 64);
-    extern __shared__ uint4 xs[];     // [2 (hi, lo)][P][NB][64]; reused for the final reduction
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ti = wave / WS, sub = wave - ti * WS;
-    const int KS = a.KS, kb = blockIdx.z;
-    const int ks0 = (int)((int64_t)kb * KS / a.Kb), ks1 = (int)((int64_t)(kb + 1) * KS / a.Kb);
-    const int rt = blockIdx.x * R + ti;
-    const int rtc = min(rt, a.n_tiles - 1);
-    const int bt0 = blockIdx.y * NB;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-    floatx4_t acc_h[NB], acc_l[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) { acc_h[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; acc_l[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f}; }
-
-    for (int kp = ks0; kp < ks1; kp += P) {
-        // All loads are unconditional, at clamped (always valid) addresses.  The staged window of P
-        // k-steps starts at xbase, the wave's window of PW steps at kbase (both pulled back to stay
-        // inside the matrix, KS >= P); steps outside the wave's share of [kp, min(kp + P, ks1)) are
-        // nulled through the weights.  Batch rows past the live batch re-read the last live row.
-        const int xbase = max(0, min(kp, KS - P));
-        {
-            uint4 r[VPT];
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                const int v = i * (kXlWaves * 64) + tid;
-                const int ln = v & 63, nb = (v >> 6) % NB, st = ((v >> 6) / NB) % P, half = (v >> 6) / (NB * P);
-                const int bsel = min((bt0 + nb) * 16 + (ln & 15), a.B - 1);
-                const uint4 *src = half ? a.xlo : a.xhi;
-                r[i] = src[((int64_t)(bsel >> 4) * KS + xbase + st) * 64 + (ln >> 4) * 16 + (bsel & 15)];
-            }
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) xs[i * (kXlWaves * 64) + tid] = r[i];
-        }
-        const int my0 = kp + sub * PW, my1 = min(ks1, my0 + PW);
-        const int kbase = max(0, min(my0, KS - PW));
-        const uint4 *wp = a.w + ((int64_t)rtc * KS + kbase) * 64 + lane;
-        uint4 w[PW];
-#pragma unroll
-        for (int u = 0; u < PW; ++u) w[u] = wp[u * 64];
-#pragma unroll
-        for (int u = 0; u < PW; ++u) if (kbase + u < my0 || kbase + u >= my1) w[u] = zero4;
-        __syncthreads();
-        const int slot0 = kbase - xbase;
-#pragma unroll
-        for (int u = 0; u < PW; ++u) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const uint4 h = xs[((0 * P + slot0 + u) * NB + nb) * 64 + lane];
-                const uint4 l = xs[((1 * P + slot0 + u) * NB + nb) * 64 + lane];
-                acc_h[nb] = mfma16(w[u], h, acc_h[nb]);
-                acc_l[nb] = mfma16(w[u], l, acc_l[nb]);
-            }
-        }
-        __syncthreads();
-    }
-
-    float4 v[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-        v[nb] = make_float4(acc_h[nb][0] + acc_l[nb][0], acc_h[nb][1] + acc_l[nb][1], acc_h[nb][2] + acc_l[nb][2],
-                            acc_h[nb][3] + acc_l[nb][3]);
-    if (WS > 1) {
-        float4 *red = reinterpret_cast<float4 *>(xs);   // [wave][NB][64]; the last barrier above freed xs
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) red[(wave * NB + nb) * 64 + lane] = v[nb];
-        __syncthreads();
-        if (sub != 0) return;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-            for (int s2 = 1; s2 < WS; ++s2) {
-                const float4 t = red[((wave + s2) * NB + nb) * 64 + lane];
-                v[nb].x += t.x; v[nb].y += t.y; v[nb].z += t.z; v[nb].w += t.w;
-            }
-        }
-    }
-    if (rt >= a.n_tiles) return;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int b = (bt0 + nb) * 16 + (lane & 15);
-        if (a.Kb == 1) gemm_epilogue<MODE>(a, rt, lane >> 4, b, v[nb]);
-        else store_partial(a, kb, rt, lane >> 4, b, v[nb]);
     }
 }
 
@@ -724,44 +518,6 @@ hipError_t launch_xs(const GemmArgs &a, int mode, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int NB, int MT>
-hipError_t launch_tiled(const GemmArgs &a, int mode, hipStream_t s)
-{
-    const dim3 grid((a.n_tiles + kTileWaves * MT - 1) / (kTileWaves * MT), (a.B + NB * 16 - 1) / (NB * 16), a.Kb);
-    const size_t lds = (size_t)2 * 2 * kTileS * NB * 64 * sizeof(uint4);
-    switch (mode) {
-    case kGemmStore: gemm_tiled_kernel<NB, MT, kGemmStore><<<grid, kTileWaves * 64, lds, s>>>(a); break;
-    case kGemmAccum: gemm_tiled_kernel<NB, MT, kGemmAccum><<<grid, kTileWaves * 64, lds, s>>>(a); break;
-    case kGemmQKV: gemm_tiled_kernel<NB, MT, kGemmQKV><<<grid, kTileWaves * 64, lds, s>>>(a); break;
-    default: gemm_tiled_kernel<NB, MT, kGemmSwiGLU><<<grid, kTileWaves * 64, lds, s>>>(a); break;
-    }
-    return hipGetLastError();
-}
-
-template <int WS>
-hipError_t launch_xl(const GemmArgs &a, int mode, hipStream_t s)
-{
-    constexpr int R = kXlWaves / WS;
-    const dim3 grid((a.n_tiles + R - 1) / R, (a.B + kXlNB * 16 - 1) / (kXlNB * 16), a.Kb);
-    constexpr size_t lds = (size_t)2 * kXlP * kXlNB * 64 * sizeof(uint4);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xl_kernel<WS, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    switch (mode) {
-    case kGemmStore: gemm_xl_kernel<WS, kGemmStore><<<grid, kXlWaves * 64, lds, s>>>(a); break;
-    case kGemmAccum: gemm_xl_kernel<WS, kGemmAccum><<<grid, kXlWaves * 64, lds, s>>>(a); break;
-    case kGemmQKV: gemm_xl_kernel<WS, kGemmQKV><<<grid, kXlWaves * 64, lds, s>>>(a); break;
-    default: gemm_xl_kernel<WS, kGemmSwiGLU><<<grid, kXlWaves * 64, lds, s>>>(a); break;
-    }
-    return hipGetLastError();
-}
-
 template <int NW, int WC, int RBT, int RA, int D>
 hipError_t launch_xb(const GemmArgs &a, int mode, hipStream_t s)
 {
@@ -806,40 +562,16 @@ static void plan_xb(int n_tiles, int KS, int B, GemmPlan &p)
     p.Kb = kb; p.Rg = rg; p.NB = sh.NBT; p.MT = sh.NW;
 }
 
-// tuning knob: PAT_GEMM_XB_MIN_BATCH in the environment moves the switch-over batch
-static int xb_min_batch_default()
-{
-    const char *e = getenv("PAT_GEMM_XB_MIN_BATCH");
-    return e && atoi(e) > 32 ? atoi(e) : 33;
-}
-static int g_xb_min_batch = xb_min_batch_default();
-void gemm_set_xb_min_batch(int b) { g_xb_min_batch = b; }
-
 GemmPlan gemm_plan(int n_tiles, int KS, int B)
 {
-    GemmPlan p{1, 1, 4, 1, kAlgoXs};
+    GemmPlan p{1, 1, 1, 16, kAlgoXs};
     if (B <= 32) {
         p.Kb = 1;                                              // a workgroup walks all of K itself
         p.Rg = n_tiles < g_target_wgs ? n_tiles : g_target_wgs;
-    } else if (B >= g_xb_min_batch && KS >= 16) {
+        p.NB = B <= 16 ? 1 : 2; p.MT = B <= 16 ? 16 : 8;
+    } else {
         p.algo = kAlgoXb;
         plan_xb(n_tiles, KS, B, p);
-    } else if (KS >= kXlP) {
-        // batch groups of 64 rows; 16 / WS row tiles per workgroup; widen WS, then split K, until the
-        // chip is covered (the partial sums of a narrow matrix are small)
-        p.algo = kAlgoXl;
-        p.NB = kXlNB;
-        const int bgroups = (B + 63) / 64;
-        int ws = 1, kb = 1;
-        auto wgs = [&]() { return ((n_tiles * ws + kXlWaves - 1) / kXlWaves) * bgroups * kb; };
-        while (wgs() < g_target_wgs && ws < 4) ws *= 2;
-        while (wgs() < g_target_wgs && KS / (kb * 2) >= 2 * kXlP && kb < 8) kb *= 2;
-        p.MT = ws;      // waves per row tile
-        p.Kb = kb;
-        p.Rg = wgs();
-    } else {
-        p.algo = kAlgoTiled;
-        p.NB = 4; p.MT = 1; p.Kb = 1; p.Rg = 1;               // tiny K: the generic tiled kernel
     }
     return p;
 }
@@ -847,7 +579,7 @@ GemmPlan gemm_plan(int n_tiles, int KS, int B)
 hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
 {
     if (a0.B <= 0 || a0.n_tiles <= 0) return hipSuccess;
-    if (a0.B > 256) return hipErrorInvalidValue;
+    if (a0.B > 256 || a0.KS < 1) return hipErrorInvalidValue;
     GemmArgs a = a0;
     const GemmPlan p = gemm_plan(a.n_tiles, a.KS, a.B);
     a.Kb = p.Kb; a.Rg = p.Rg;
@@ -855,11 +587,8 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
     if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
     if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
-    hipError_t e;
-    if (p.algo == kAlgoXb)
-        e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s) : p.NB == 8 ? launch_xb<8, 2, 4, 4, 4>(a, mode, s) : launch_xb<8, 2, 8, 4, 2>(a, mode, s);
-    else if (p.algo == kAlgoXl) e = p.MT == 1 ? launch_xl<1>(a, mode, s) : p.MT == 2 ? launch_xl<2>(a, mode, s) : launch_xl<4>(a, mode, s);
-    else e = launch_tiled<4, 1>(a, mode, s);
+    const hipError_t e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s)
+                       : p.NB == 8 ? launch_xb<8, 2, 4, 4, 4>(a, mode, s) : launch_xb<8, 2, 8, 4, 2>(a, mode, s);
     if (e != hipSuccess || a.Kb == 1) return e;
     const int64_t n = (int64_t)a.B * a.n_tiles * 4;
     const unsigned blocks = (unsigned)((n + 255) / 256);

@@ -719,7 +719,7 @@ int pat_op_gemm_plan(int32_t n, int32_t k, int32_t b, int32_t plan[4])
 {
     if (!plan || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256) return PAT_EINVAL;
     const GemmPlan p = gemm_plan(cdiv(n, 16), k / 32, b);
-    plan[0] = p.algo; plan[1] = p.Kb; plan[2] = p.Rg; plan[3] = p.algo == kAlgoXs ? (b <= 16 ? 1 : 2) : p.NB;
+    plan[0] = p.algo; plan[1] = p.Kb; plan[2] = p.Rg; plan[3] = p.NB;
     return PAT_OK;
 }
 

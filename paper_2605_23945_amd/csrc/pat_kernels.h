@@ -36,11 +36,10 @@ struct GemmArgs {
     int Kb, Rg;                // set by launch_gemm from gemm_plan
 };
 // How a [16 n_tiles, 32 KS] projection at live batch B is cut: K slices across workgroups and row groups.
-enum GemmAlgo { kAlgoXs = 0, kAlgoXl = 1, kAlgoTiled = 2, kAlgoXb = 3 };
+enum GemmAlgo { kAlgoXs = 0, kAlgoXb = 3 };
 struct GemmPlan { int Kb, Rg, NB, MT, algo; };
 GemmPlan gemm_plan(int n_tiles, int KS, int B);
 void gemm_set_compute_units(int n);
-void gemm_set_xb_min_batch(int b);   // live batch from which the full-batch kernel replaces the batch-grouped one
 
 hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s);
 // as above for a QKV matrix: within each of the first rope_rows / d heads, row p holds natural row
