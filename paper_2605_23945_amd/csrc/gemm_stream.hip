@@ -191,7 +191,8 @@ template <int NB, int UK, int TB, int kXsWaves, int MODE>
 __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 {
     extern __shared__ float4 red[];   // [TB][kXsWaves][NB][64]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave index as a scalar: what derives from it (k share, slots, tile) stays in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KS = a.KS, Rg = a.Rg;
     const int rg = blockIdx.x;
     // the wave's contiguous share of the k-steps (shares differ by at most one step)
