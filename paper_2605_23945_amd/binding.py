@@ -59,11 +59,32 @@ class pat_grid_row(C.Structure):
                 ("tokens_per_s", C.c_double), ("algo_bytes", C.c_double), ("hbm_frac", C.c_double)]
 
 
+class pat_prefill_row(C.Structure):
+    _fields_ = [("tp_degree", C.c_int32), ("batch", C.c_int32), ("length", C.c_int32), ("latency_us", C.c_double)]
+
+
+class pat_switch_input(C.Structure):
+    _fields_ = [("tp", C.c_int32), ("tp_list", C.POINTER(C.c_int32)), ("n_tp", C.c_int32), ("n_gpus", C.c_int32),
+                ("group_batch", C.POINTER(C.c_int32)), ("group_context", C.POINTER(C.c_double)), ("n_groups", C.c_int32),
+                ("l_max", C.c_int32), ("l_gen", C.c_int32), ("lengths", C.POINTER(C.c_int32)), ("n_lengths", C.c_int32),
+                ("n_layers", C.c_int32), ("hidden", C.c_int32), ("bytes_per_elem", C.c_int32),
+                ("net_bytes_per_s", C.c_double), ("fixed_us", C.POINTER(C.c_double)),
+                ("prefill", C.POINTER(pat_prefill_row)), ("n_prefill", C.c_int32)]
+
+
+class pat_switch_decision(C.Structure):
+    _fields_ = [("do_switch", C.c_int32), ("tp_new", C.c_int32), ("t_cur_us", C.c_double), ("t_best_us", C.c_double),
+                ("t_rem_us", C.POINTER(C.c_double)), ("t_switch_us", C.POINTER(C.c_double)),
+                ("t_total_us", C.POINTER(C.c_double))]
+
+
 EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_final", "pat_decode_admit",
            "pat_kv_write", "pat_kv_read", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax"]
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
+           "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
+           "pat_kv_move_seconds", "pat_rms_length"]
 
 _lib = None
 
@@ -110,6 +131,17 @@ def load_library() -> C.CDLL:
     lib.pat_op_gemm_plan.restype = C.c_int
     lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
+    dp = C.POINTER(C.c_double)
+    lib.pat_predictor_fit.argtypes = [C.POINTER(pat_grid_row), C.c_int32, C.POINTER(vp)]
+    lib.pat_predictor_destroy.argtypes = [vp]
+    lib.pat_predictor_destroy.restype = None
+    lib.pat_predictor_line.argtypes = [vp, C.c_int32, C.c_int32, dp, dp]
+    lib.pat_predictor_query.argtypes = [vp, C.c_int32, C.c_int32, C.c_double, dp]
+    lib.pat_switch_decide.argtypes = [vp, C.POINTER(pat_switch_input), C.POINTER(pat_switch_decision)]
+    lib.pat_kv_move_seconds.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double]
+    lib.pat_kv_move_seconds.restype = C.c_double
+    lib.pat_rms_length.argtypes = [i32p, C.c_int32]
+    lib.pat_rms_length.restype = C.c_double
     _lib = lib
     return lib
 
@@ -325,3 +357,88 @@ def unpack_act(hi, lo, b, k):
         a = t.view(torch.bfloat16).float().cpu().numpy().reshape(bt, KS, 4, 16, 8)   # [tile, ks, g, r, j]
         return a.transpose(0, 3, 1, 2, 4).reshape(bt * 16, k)[:b].astype(np.float64)
     return one(hi) + one(lo)
+
+
+class Predictor:
+    """Latency predictor fitted to grid rows (include/pat_switch.h); argument marshalling only.
+
+    rows: a ctypes array of pat_grid_row (as pat_profile_grid returns) or an iterable of
+    (tp, batch, sum_context, mean_us) tuples of measured points."""
+
+    def __init__(self, rows):
+        self._lib = load_library()
+        if not (isinstance(rows, C.Array) and rows._type_ is pat_grid_row):
+            rows = list(rows)
+            arr = (pat_grid_row * len(rows))()
+            for r, (tp, b, t, us) in zip(arr, rows):
+                r.tp_degree, r.batch, r.sum_context, r.mean_us, r.skipped = int(tp), int(b), int(t), float(us), 0
+            rows = arr
+        self._h = C.c_void_p()
+        rc = self._lib.pat_predictor_fit(rows, len(rows), C.byref(self._h))
+        if rc:
+            raise PatError(rc, "pat_predictor_fit")
+
+    def close(self):
+        if self._h:
+            self._lib.pat_predictor_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def pat_predictor_line(self, tp, batch):
+        a, b = C.c_double(), C.c_double()
+        rc = self._lib.pat_predictor_line(self._h, tp, batch, C.byref(a), C.byref(b))
+        if rc:
+            raise PatError(rc, "pat_predictor_line")
+        return a.value, b.value
+
+    def pat_predictor_query(self, tp, batch, sum_context):
+        out = C.c_double()
+        rc = self._lib.pat_predictor_query(self._h, tp, batch, float(sum_context), C.byref(out))
+        if rc:
+            raise PatError(rc, "pat_predictor_query")
+        return out.value
+
+    def pat_switch_decide(self, tp, tp_list, groups, l_max, l_gen, lengths, model, fixed_us, net_bytes_per_s, n_gpus,
+                          prefill=None):
+        """groups: [(batch, context tokens)] per DP group; model = (n_layers, hidden, bytes per element);
+        fixed_us: {(tp_from, tp_to): microseconds}; prefill: [(tp, batch, length, microseconds)] or None.
+        Returns (do_switch, tp_new, t_cur_us, t_best_us, [(tp, t_rem, t_switch, t_total)])."""
+        n = len(tp_list)
+        inp = pat_switch_input()
+        tpl = (C.c_int32 * n)(*tp_list)
+        gb = (C.c_int32 * len(groups))(*[int(g[0]) for g in groups])
+        gc = (C.c_double * len(groups))(*[float(g[1]) for g in groups])
+        ln = (C.c_int32 * max(1, len(lengths)))(*[int(x) for x in lengths])
+        fx = (C.c_double * (n * n))(*[float(fixed_us.get((a, b), 0.0)) for a in tp_list for b in tp_list])
+        inp.tp, inp.tp_list, inp.n_tp, inp.n_gpus = tp, tpl, n, n_gpus
+        inp.group_batch, inp.group_context, inp.n_groups = gb, gc, len(groups)
+        inp.l_max, inp.l_gen, inp.lengths, inp.n_lengths = l_max, l_gen, ln, len(lengths)
+        inp.n_layers, inp.hidden, inp.bytes_per_elem = model
+        inp.net_bytes_per_s, inp.fixed_us = float(net_bytes_per_s), fx
+        if prefill:
+            pf = (pat_prefill_row * len(prefill))()
+            for r, (ptp, pb, pl, pus) in zip(pf, prefill):
+                r.tp_degree, r.batch, r.length, r.latency_us = int(ptp), int(pb), int(pl), float(pus)
+            inp.prefill, inp.n_prefill = pf, len(prefill)
+        rem, sw, tot = (C.c_double * n)(), (C.c_double * n)(), (C.c_double * n)()
+        out = pat_switch_decision()
+        out.t_rem_us, out.t_switch_us, out.t_total_us = rem, sw, tot
+        rc = self._lib.pat_switch_decide(self._h, C.byref(inp), C.byref(out))
+        if rc:
+            raise PatError(rc, "pat_switch_decide")
+        return bool(out.do_switch), out.tp_new, out.t_cur_us, out.t_best_us, [(tp_list[j], rem[j], sw[j], tot[j]) for j in range(n)]
+
+
+def pat_kv_move_seconds(lengths, n_layers, hidden, bytes_per_elem, tp_src, net_bytes_per_s):
+    ln = (C.c_int32 * max(1, len(lengths)))(*[int(x) for x in lengths])
+    return load_library().pat_kv_move_seconds(ln, len(lengths), n_layers, hidden, bytes_per_elem, tp_src, float(net_bytes_per_s))
+
+
+def pat_rms_length(lengths):
+    ln = (C.c_int32 * len(lengths))(*[int(x) for x in lengths])
+    return load_library().pat_rms_length(ln, len(lengths))
