@@ -378,3 +378,24 @@ def test_profile_grid_protocol():
     assert [r["skipped"] for r in rows] == [0, 0, 0, 0, 0, 0, 0, 0, 1]
     assert dec.pat_get_state()["live"] == 0                               # the sweep leaves an empty batch
     dec.close()
+
+
+def test_predictor_fitted_to_a_measured_grid_predicts_a_held_out_point():
+    """The latency predictor (host C++) on rows this GPU just measured: lines reproduce their own
+    points closely and a held-out (batch, length) point inside the grid is predicted to within 25 %."""
+    shard = pi.CONFIGS["7b_tp1"]["shard"].with_layers(4)
+    pat = _pat()
+    dec = make_decoder(shard, 16, 2048 + 128, 16 * 2048 + 16 * 128)
+    pat.load_synthetic_weights(dec, shard)
+    rows = dec.pat_profile_grid([1, 16], [256, 1024, 2048], 1 << 16, steps=20, warmup=3, reps=2)
+    assert all(r["skipped"] == 0 for r in rows)
+    pred = pat.Predictor([(r["tp_degree"], r["batch"], r["sum_context"], r["mean_us"]) for r in rows])
+    for r in rows:
+        assert abs(pred.pat_predictor_query(1, r["batch"], r["sum_context"]) / r["mean_us"] - 1.0) < 0.10
+    a1, b1 = pred.pat_predictor_line(1, 16)
+    assert b1 > 0.0                                    # more context tokens cost more time
+    held = dec.pat_profile_grid([4], [1024], 1 << 16, steps=20, warmup=3, reps=2)[0]
+    p = pred.pat_predictor_query(1, 4, held["sum_context"])
+    print(f"held-out B=4 L=1024: measured {held['mean_us']:.1f} us, predicted {p:.1f} us")
+    assert abs(p / held["mean_us"] - 1.0) < 0.25
+    dec.close()
