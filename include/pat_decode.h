@@ -127,6 +127,28 @@ int pat_decode_admit(pat_ctx *ctx, int32_t n, const int32_t *seq_id, const int32
 int pat_kv_write(pat_ctx *ctx, int32_t slot, int32_t layer, const void *k_dev, const void *v_dev, int32_t n_tokens);
 int pat_kv_read(pat_ctx *ctx, int32_t slot, int32_t layer, void *k_dev, void *v_dev, int32_t n_tokens);
 
+/* KV migration, the local half (Sec. 4.2, "State handling for unfinished samples": valid KV
+ * states of unfinished samples are gathered layer-wise and each target rank slices out the
+ * head partition it needs; copies only, so no floating-point error).
+ *
+ * pat_kv_extract gathers the valid K/V of `n` live slots (host array `slots`, in this order,
+ * no repeats) for layers [layer0, layer0 + n_layers) and this shard's KV heads
+ * [head0, head0 + n_heads) into `buf` (device, 16-byte aligned, buf_bytes >=
+ * n_layers * 2 * n_heads * T * head_dim * 2 with T = sum of the slots' context lengths, returned in
+ * *t_sel_out if not NULL), laid out [layer][K|V][head][token][head_dim] bf16 with the slots'
+ * tokens back to back (buf may be NULL when T = 0).  The pool is not changed.
+ *
+ * pat_kv_inject is the inverse for slots admitted with their context lengths (pat_decode_admit
+ * gives them pages): it fills KV heads [pool_head0, pool_head0 + n_heads) of those slots from the
+ * heads [buf_head0, buf_head0 + n_heads) of a buffer in the same layout holding buf_heads heads
+ * and t_sel tokens per head (t_sel must equal the slots' total).
+ *
+ * Both enqueue one copy kernel and wait for it (the staging of the slot list is reused). */
+int pat_kv_extract(pat_ctx *ctx, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers, int32_t head0,
+                   int32_t n_heads, void *buf, int64_t buf_bytes, int64_t *t_sel_out);
+int pat_kv_inject(pat_ctx *ctx, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers, int32_t pool_head0,
+                  int32_t n_heads, const void *buf, int32_t buf_heads, int32_t buf_head0, int64_t t_sel);
+
 /* One decode step over the live batch: embedding, n_layers x (RMSNorm, QKV,
  * rotary + KV append, attention over the paged cache, O + residual, RMSNorm,
  * gate/up + SiLU*mul, down + residual), final RMSNorm, vocabulary-slice logits,

@@ -251,3 +251,22 @@ class OracleDecoder:
             setattr(self, name, getattr(self, name)[keep].copy())
         self.kc = [self.kc[j] for j in keep]; self.vc = [self.vc[j] for j in keep]
         return nb
+
+
+def kv_extract(od: OracleDecoder, slots, layer0, n_layers, head0, n_heads):
+    """Valid K/V of the chosen live slots as one buffer [layer][K|V][head][token][d] (uint16 bf16 bits),
+    the tokens of the slots back to back in the order given: the send buffer of the paper's KV
+    migration (Sec. 4.2, "All-Gather and Slice": only valid states of unfinished samples move, as
+    plain copies).  Written out element by element."""
+    d = od.dims[4]
+    t_sel = int(sum(int(od.kv_len[s]) for s in slots))
+    out = np.zeros((n_layers, 2, n_heads, t_sel, d), np.uint16)
+    for l in range(n_layers):
+        for h in range(n_heads):
+            t = 0
+            for s in slots:
+                for tok in range(int(od.kv_len[s])):
+                    out[l, 0, h, t] = od.kc[s][layer0 + l][tok, head0 + h]
+                    out[l, 1, h, t] = od.vc[s][layer0 + l][tok, head0 + h]
+                    t += 1
+    return out

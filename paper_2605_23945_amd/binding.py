@@ -79,7 +79,7 @@ class pat_switch_decision(C.Structure):
 
 
 EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_final", "pat_decode_admit",
-           "pat_kv_write", "pat_kv_read", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
+           "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
            "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
@@ -105,6 +105,8 @@ def load_library() -> C.CDLL:
     lib.pat_decode_admit.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p]
     lib.pat_kv_write.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
     lib.pat_kv_read.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
+    lib.pat_kv_extract.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int64, C.POINTER(C.c_int64)]
+    lib.pat_kv_inject.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, C.c_int32, C.c_int64]
     lib.pat_decode_step.argtypes = [vp, C.POINTER(pat_step_report), vp, vp]
     lib.pat_kv_compact.argtypes = [vp, i32p]
     lib.pat_get_state.argtypes = [vp, i32p] + [i32p] * 6
@@ -230,6 +232,29 @@ class Decoder:
         v = torch.empty_like(k)
         self._chk(self.lib.pat_kv_read(self.ctx, slot, layer, _ptr(k), _ptr(v), n_tokens))
         return k, v
+
+    def pat_kv_extract(self, slots, layer0=0, n_layers=None, head0=0, n_heads=None, buf=None):
+        """Returns (buf, T): buf a bf16 tensor [n_layers, 2, n_heads, T, d] on the device."""
+        import torch
+        n_layers = self.cfg.n_layers - layer0 if n_layers is None else n_layers
+        n_heads = self.hkv - head0 if n_heads is None else n_heads
+        if buf is None:
+            st = self.pat_get_state()
+            t = int(sum(int(st["kv_len"][s]) for s in slots if 0 <= s < st["live"]))     # the library rejects the rest
+            buf = torch.empty((n_layers, 2, n_heads, t, self.d), dtype=torch.bfloat16, device=self.device)
+        t_sel = C.c_int64()
+        sl, slp = _i32(slots)
+        self._chk(self.lib.pat_kv_extract(self.ctx, len(sl), slp, layer0, n_layers, head0, n_heads, _ptr(buf),
+                                          buf.numel() * 2, C.byref(t_sel)))
+        return buf, t_sel.value
+
+    def pat_kv_inject(self, slots, buf, layer0=0, pool_head0=0, n_heads=None, buf_head0=0):
+        """buf: bf16 tensor [n_layers, 2, buf_heads, T, d] (contiguous) on the device."""
+        n_layers, _, buf_heads, t, _ = buf.shape
+        n_heads = min(self.hkv - pool_head0, buf_heads - buf_head0) if n_heads is None else n_heads
+        sl, slp = _i32(slots)
+        self._chk(self.lib.pat_kv_inject(self.ctx, len(sl), slp, layer0, n_layers, pool_head0, n_heads,
+                                         _ptr(buf), buf_heads, buf_head0, t))
 
     def pat_decode_step(self, report=True, next_tok=None, logits=None):
         rep = pat_step_report()

@@ -28,7 +28,7 @@ struct Shard {
 };
 
 struct WorkLayout {   // byte offsets inside the work arena
-    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
+    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, sel, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
     int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, tmp;
     int64_t total;
     int64_t max_chunks;
@@ -143,6 +143,7 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     w->b_hi = take(packed_x_bytes(MB, kb));
     w->b_lo = take(packed_x_bytes(MB, kb));
     w->qkv = take((int64_t)MB * s.qkv_rows * 4);
+    w->sel = take((int64_t)2 * MB * 4);                 // selected slots and their token offsets (KV extract / inject)
     {   // scratch for K-slice partial sums of the projections: the largest any (matrix, batch) needs
         const int mats[5][2] = {{s.qkv_rows / 16, s.H / 32}, {s.H / 16, s.hq * s.d / 32}, {2 * s.F / 16, s.H / 32},
                                 {s.H / 16, s.F / 32}, {s.Vs / 16, s.H / 32}};
@@ -419,6 +420,63 @@ int pat_kv_write(pat_ctx *c, int32_t slot, int32_t layer, const void *k, const v
 }
 
 int pat_kv_read(pat_ctx *c, int32_t slot, int32_t layer, void *k, void *v, int32_t n) { return kv_copy(c, slot, layer, k, v, n, 0); }
+
+// Shared by pat_kv_extract / pat_kv_inject: validates the selection, stages (slots, token offsets) and
+// launches the copy.
+static int kv_move(pat_ctx *c, const char *what, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers,
+                   int32_t pool_head0, int32_t n_heads, void *buf, int32_t buf_heads, int32_t buf_head0, int64_t buf_bytes,
+                   int64_t t_expected, int64_t *t_sel_out, int to_pool)
+{
+    if (!c) return PAT_EINVAL;
+    const Shard &s = c->sh;
+    if (n <= 0 || !slots) return fail(c, PAT_EINVAL, "%s: bad arguments", what);
+    if (n > c->cfg.max_batch) return fail(c, PAT_EINVAL, "%s: %d slots selected, max_batch is %d", what, n, c->cfg.max_batch);
+    if (layer0 < 0 || n_layers < 1 || layer0 + n_layers > s.NL) return fail(c, PAT_EINVAL, "%s: layers [%d, %d) outside [0, %d)", what, layer0, layer0 + n_layers, s.NL);
+    if (pool_head0 < 0 || n_heads < 1 || pool_head0 + n_heads > s.hkv) return fail(c, PAT_EINVAL, "%s: KV heads [%d, %d) outside this shard's [0, %d)", what, pool_head0, pool_head0 + n_heads, s.hkv);
+    if (buf_head0 < 0 || buf_head0 + n_heads > buf_heads) return fail(c, PAT_EINVAL, "%s: buffer heads [%d, %d) outside [0, %d)", what, buf_head0, buf_head0 + n_heads, buf_heads);
+    if ((uintptr_t)buf & 15) return fail(c, PAT_EINVAL, "%s: buffer not 16-byte aligned", what);
+    int64_t t_sel = 0; int max_pages_sel = 0;
+    int32_t *p = c->pinned;
+    const int MB = c->cfg.max_batch;
+    for (int i = 0; i < n; ++i) {
+        if (slots[i] < 0 || slots[i] >= c->live) return fail(c, PAT_EINVAL, "%s: slot %d is not live", what, slots[i]);
+        for (int j = 0; j < i; ++j) if (slots[j] == slots[i]) return fail(c, PAT_EINVAL, "%s: slot %d selected twice", what, slots[i]);
+        if (t_sel > INT32_MAX) return fail(c, PAT_EINVAL, "%s: more than 2^31 tokens selected", what);
+        p[i] = slots[i]; p[MB + i] = (int32_t)t_sel;
+        t_sel += c->kv_len[slots[i]];
+        max_pages_sel = std::max(max_pages_sel, cdiv(c->kv_len[slots[i]], c->cfg.page_tokens));
+    }
+    if (t_expected >= 0 && t_sel != t_expected) return fail(c, PAT_EINVAL, "%s: the slots hold %lld tokens, the buffer %lld", what, (long long)t_sel, (long long)t_expected);
+    const int64_t need = (int64_t)n_layers * 2 * buf_heads * t_sel * s.d * 2;
+    if (buf_bytes >= 0 && buf_bytes < need) return fail(c, PAT_EINVAL, "%s: buffer of %lld bytes, %lld needed", what, (long long)buf_bytes, (long long)need);
+    if (t_sel > 0 && !buf) return fail(c, PAT_EINVAL, "%s: NULL buffer", what);
+    if (t_sel_out) *t_sel_out = t_sel;
+    if (t_sel == 0) return PAT_OK;
+    int32_t *sel = at<int32_t>(c->bufs.work, c->wl.sel);
+    PAT_HIP(c, hipMemcpyAsync(sel, p, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    PAT_HIP(c, hipMemcpyAsync(sel + MB, p + MB, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    KvMoveArgs a{};
+    a.kv = c->kv; a.slots = sel; a.tok_off = sel + MB; a.kv_len = c->st.kv_len; a.page_table = c->st.page_table;
+    a.max_pages = s.max_pages; a.layer0 = layer0; a.n_layers = n_layers; a.pool_head0 = pool_head0; a.n_heads = n_heads;
+    a.buf = (uint16_t *)buf; a.buf_heads = buf_heads; a.buf_head0 = buf_head0; a.t_sel = t_sel; a.to_pool = to_pool;
+    PAT_HIP(c, launch_kv_move(a, n, max_pages_sel, c->stream));
+    PAT_HIP(c, hipStreamSynchronize(c->stream));      // the staging buffer is reused by the next call
+    return PAT_OK;
+}
+
+int pat_kv_extract(pat_ctx *c, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers, int32_t head0,
+                   int32_t n_heads, void *buf, int64_t buf_bytes, int64_t *t_sel_out)
+{
+    return kv_move(c, "kv extract", n, slots, layer0, n_layers, head0, n_heads, buf, n_heads, 0, buf_bytes, -1, t_sel_out, 0);
+}
+
+int pat_kv_inject(pat_ctx *c, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers, int32_t pool_head0,
+                  int32_t n_heads, const void *buf, int32_t buf_heads, int32_t buf_head0, int64_t t_sel)
+{
+    if (t_sel < 0) return c ? fail(c, PAT_EINVAL, "kv inject: negative token count") : PAT_EINVAL;
+    return kv_move(c, "kv inject", n, slots, layer0, n_layers, pool_head0, n_heads, const_cast<void *>(buf), buf_heads,
+                   buf_head0, -1, t_sel, nullptr, 1);
+}
 
 int pat_step_algo_bytes(pat_ctx *c, double *weight_bytes, double *kv_bytes)
 {

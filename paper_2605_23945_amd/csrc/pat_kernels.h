@@ -91,6 +91,17 @@ hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, 
 hipError_t launch_compact(const StateArrays &st, int B, hipStream_t s);
 hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, uint16_t *k, uint16_t *v, int n_tokens,
                           int to_pool, hipStream_t s);
+struct KvMoveArgs {
+    KvLayout kv;
+    const int32_t *slots, *tok_off;        // device: selected slots and the token offset of each in the buffer
+    const int32_t *kv_len, *page_table;    // device state
+    int max_pages, layer0, n_layers, pool_head0, n_heads;
+    uint16_t *buf;                         // [n_layers][2][buf_heads][t_sel][d] bf16
+    int buf_heads, buf_head0;
+    int64_t t_sel;
+    int to_pool, pages_per_block;
+};
+hipError_t launch_kv_move(const KvMoveArgs &a, int n_slots, int max_pages_sel, hipStream_t s);
 hipError_t launch_kv_fill(const KvLayout &kv, int n_layers, uint64_t seed, hipStream_t s);
 
 }  // namespace pat

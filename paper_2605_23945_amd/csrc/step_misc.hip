@@ -213,6 +213,33 @@ __global__ void kv_copy_kernel(KvLayout kv, int layer, const int32_t *pt_row, ui
     if (to_pool) { *pk = *fk; *pv = *fv; } else { *fk = *pk; *fv = *pv; }
 }
 
+// Valid K/V of selected slots <-> one contiguous buffer [layer][K|V][head][token][d], the tokens of
+// the selected slots back to back: the local half of the KV migration (gather what the unfinished
+// samples hold, or fill a head slice of freshly admitted slots from a gathered buffer).  Pure 16-byte
+// copies.  A (page, head) block is contiguous on both sides.  grid: x = selected slot,
+// y = (layer, K|V, head), z = run of pages.
+__global__ __launch_bounds__(256) void kv_move_kernel(KvMoveArgs a)
+{
+    const int i = blockIdx.x;
+    const int slot = a.slots[i];
+    const int L = a.kv_len[slot];
+    const int h = blockIdx.y % a.n_heads, kvsel = (blockIdx.y / a.n_heads) & 1, l = blockIdx.y / (2 * a.n_heads);
+    const int P = a.kv.P, d = a.kv.d;
+    const int n_pages = (L + P - 1) / P;
+    const int p0 = blockIdx.z * a.pages_per_block, p1 = min(p0 + a.pages_per_block, n_pages);
+    const int vec_per_tok = d >> 3;
+    for (int p = p0; p < p1; ++p) {
+        const int page = a.page_table[(int64_t)slot * a.max_pages + p];
+        const int n_vec = min(P, L - p * P) * vec_per_tok;
+        uint4 *pool = reinterpret_cast<uint4 *>(a.kv.pool + a.kv.base(a.layer0 + l, kvsel) + (int64_t)page * a.kv.page_elems() +
+                                                (int64_t)(a.pool_head0 + h) * P * d);
+        uint4 *buf = reinterpret_cast<uint4 *>(a.buf + ((((int64_t)l * 2 + kvsel) * a.buf_heads + a.buf_head0 + h) * a.t_sel +
+                                                        a.tok_off[i] + (int64_t)p * P) * d);
+        if (a.to_pool) { for (int v = threadIdx.x; v < n_vec; v += 256) pool[v] = buf[v]; }
+        else { for (int v = threadIdx.x; v < n_vec; v += 256) buf[v] = pool[v]; }
+    }
+}
+
 __device__ __forceinline__ uint32_t mix32(uint32_t x)
 {
     x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
@@ -296,6 +323,17 @@ hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, 
     if (n_tokens <= 0) return hipSuccess;
     const int64_t n = (int64_t)n_tokens * (kv.hkv * kv.d / 8);
     kv_copy_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(kv, layer, pt_row, k, v, n_tokens, to_pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_move(const KvMoveArgs &a0, int n_slots, int max_pages_sel, hipStream_t s)
+{
+    if (n_slots <= 0 || a0.n_layers <= 0 || a0.n_heads <= 0 || max_pages_sel <= 0) return hipSuccess;
+    KvMoveArgs a = a0;
+    a.pages_per_block = 8;
+    const dim3 grid((unsigned)n_slots, (unsigned)(a.n_layers * 2 * a.n_heads), (unsigned)((max_pages_sel + 7) / 8));
+    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    kv_move_kernel<<<grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
