@@ -113,6 +113,15 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
  * passed this call.  Every layer and the final tensors must be loaded before
  * the first step. */
 int pat_load_layer(pat_ctx *ctx, int32_t layer, const pat_layer_weights *w);
+
+/* Weight re-slice (Sec. 4.2, "Efficient weight resharding": layer-wise All-Gather and Slice, contents
+ * unchanged, only the partitioning changes).  As pat_load_layer, but `full` holds the UNSHARDED
+ * layer (what the all-gather of the old shards returns, one layer at a time so that the scratch is
+ * bounded): wqkv [(n_q_heads + 2 n_kv_heads) d, hidden], wo [hidden, n_q_heads d], wg, wu
+ * [ffn, hidden], wd [hidden, ffn], g1, g2 [hidden].  This rank's rows and columns (from tp_degree
+ * and tp_rank of the configuration; KV heads replicated when n_kv_heads < tp_degree) are sliced out
+ * and repacked on the fly; nothing but copies, so the result equals pat_load_layer of the slices. */
+int pat_load_layer_from_full(pat_ctx *ctx, int32_t layer, const pat_layer_weights *full);
 int pat_load_final(pat_ctx *ctx, const pat_final_weights *w);
 
 /* Appends n sequences to the live batch (host arrays of n): id, the token to

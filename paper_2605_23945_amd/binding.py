@@ -78,7 +78,7 @@ class pat_switch_decision(C.Structure):
                 ("t_total_us", C.POINTER(C.c_double))]
 
 
-EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_final", "pat_decode_admit",
+EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_layer_from_full", "pat_load_final", "pat_decode_admit",
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
@@ -101,6 +101,7 @@ def load_library() -> C.CDLL:
     lib.pat_decode_query.argtypes = [C.POINTER(pat_cfg), C.POINTER(pat_mem_req)]
     lib.pat_decode_init.argtypes = [C.POINTER(pat_cfg), C.POINTER(pat_buffers), vp, C.POINTER(vp)]
     lib.pat_load_layer.argtypes = [vp, C.c_int32, C.POINTER(pat_layer_weights)]
+    lib.pat_load_layer_from_full.argtypes = [vp, C.c_int32, C.POINTER(pat_layer_weights)]
     lib.pat_load_final.argtypes = [vp, C.POINTER(pat_final_weights)]
     lib.pat_decode_admit.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p]
     lib.pat_kv_write.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
@@ -213,6 +214,11 @@ class Decoder:
     def pat_load_layer(self, layer, w: dict):
         lw = pat_layer_weights(*[_ptr(w[k]) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")])
         self._chk(self.lib.pat_load_layer(self.ctx, layer, C.byref(lw)))
+
+    def pat_load_layer_from_full(self, layer, w: dict):
+        """w: the UNSHARDED layer's tensors (same keys as pat_load_layer)."""
+        lw = pat_layer_weights(*[_ptr(w[k]) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")])
+        self._chk(self.lib.pat_load_layer_from_full(self.ctx, layer, C.byref(lw)))
 
     def pat_load_final(self, w: dict):
         fw = pat_final_weights(_ptr(w["embed"]), _ptr(w["gf"]), _ptr(w["wlm"]))

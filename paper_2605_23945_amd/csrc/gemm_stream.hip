@@ -417,7 +417,7 @@ __global__ void gemm_reduce_kernel(GemmArgs a)
 }
 
 // one thread per 16-byte vector of the packed matrix
-__global__ void pack_weight_kernel(const uint16_t *w, const uint16_t *w2, int n, int k, int KS, int64_t n_vec,
+__global__ void pack_weight_kernel(const uint16_t *w, const uint16_t *w2, int n, int k, int64_t ld, int KS, int64_t n_vec,
                                    uint4 *packed, int rope_rows, int d)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -436,7 +436,7 @@ __global__ void pack_weight_kernel(const uint16_t *w, const uint16_t *w2, int n,
         srow = head * d + ((p & 1) ? (p >> 1) + (d >> 1) : (p >> 1));
     }
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (srow < n) v = *reinterpret_cast<const uint4 *>(src + (int64_t)srow * k + kk);
+    if (srow < n) v = *reinterpret_cast<const uint4 *>(src + (int64_t)srow * ld + kk);     // ld: elements between source rows
     packed[i] = v;
 }
 
@@ -602,21 +602,21 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s)
+hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, int64_t ld, uint4 *packed, hipStream_t s)
 {
     const int rows = w2 ? 2 * n : n;
     const int KS = k / 32;
     const int64_t n_vec = (int64_t)((rows + 15) / 16) * KS * 64;
     const int64_t blocks = (n_vec + 255) / 256;
-    pack_weight_kernel<<<(unsigned)blocks, 256, 0, s>>>(w, w2, n, k, KS, n_vec, packed, 0, 1);
+    pack_weight_kernel<<<(unsigned)blocks, 256, 0, s>>>(w, w2, n, k, ld, KS, n_vec, packed, 0, 1);
     return hipGetLastError();
 }
 
-hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int rope_rows, int d, uint4 *packed, hipStream_t s)
+hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int64_t ld, int rope_rows, int d, uint4 *packed, hipStream_t s)
 {
     const int KS = k / 32;
     const int64_t n_vec = (int64_t)((n + 15) / 16) * KS * 64;
-    pack_weight_kernel<<<(unsigned)((n_vec + 255) / 256), 256, 0, s>>>(w, nullptr, n, k, KS, n_vec, packed, rope_rows, d);
+    pack_weight_kernel<<<(unsigned)((n_vec + 255) / 256), 256, 0, s>>>(w, nullptr, n, k, ld, KS, n_vec, packed, rope_rows, d);
     return hipGetLastError();
 }
 

@@ -344,10 +344,41 @@ int pat_load_layer(pat_ctx *c, int32_t layer, const pat_layer_weights *w)
     char *L = at<char>(c->bufs.weights, c->wt.layer0 + c->wt.layer_stride * layer);
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
-    PAT_HIP(c, launch_pack_weight_qkv((const uint16_t *)w->wqkv, s.qkv_rows, s.H, (s.hq + s.hkv) * s.d, s.d, (uint4 *)(L + c->wt.wqkv), c->stream));
-    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wo, nullptr, s.H, s.hq * s.d, (uint4 *)(L + c->wt.wo), c->stream));
-    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wg, (const uint16_t *)w->wu, s.F, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
-    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wd, nullptr, s.H, s.F, (uint4 *)(L + c->wt.wd), c->stream));
+    PAT_HIP(c, launch_pack_weight_qkv((const uint16_t *)w->wqkv, s.qkv_rows, s.H, s.H, (s.hq + s.hkv) * s.d, s.d, (uint4 *)(L + c->wt.wqkv), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wo, nullptr, s.H, s.hq * s.d, s.hq * s.d, (uint4 *)(L + c->wt.wo), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wg, (const uint16_t *)w->wu, s.F, s.H, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wd, nullptr, s.H, s.F, s.F, (uint4 *)(L + c->wt.wd), c->stream));
+    c->layer_loaded[layer] = 1;
+    return PAT_OK;
+}
+
+int pat_load_layer_from_full(pat_ctx *c, int32_t layer, const pat_layer_weights *w)
+{
+    if (!c) return PAT_EINVAL;
+    if (!w || layer < 0 || layer >= c->sh.NL) return fail(c, PAT_EINVAL, "layer %d outside [0, %d)", layer, c->sh.NL);
+    if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(c, PAT_EINVAL, "NULL weight pointer");
+    const Shard &s = c->sh;
+    const pat_cfg &m = c->cfg;
+    const int tp = m.tp_degree, rank = m.tp_rank, d = s.d;
+    const int Hq = m.n_q_heads, Hkv = m.n_kv_heads, Ff = m.ffn;
+    const int q0 = rank * s.hq, kv0 = Hkv >= tp ? rank * s.hkv : rank / (tp / Hkv), f0 = rank * s.F;
+    char *L = at<char>(c->bufs.weights, c->wt.layer0 + c->wt.layer_stride * layer);
+    const uint16_t *wqkv = (const uint16_t *)w->wqkv, *wo = (const uint16_t *)w->wo, *wg = (const uint16_t *)w->wg,
+                   *wu = (const uint16_t *)w->wu, *wd = (const uint16_t *)w->wd;
+    PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    // q, k and v rows of this rank are three row ranges of the full matrix; each fills whole 16-row tiles
+    // of the packed matrix (head_dim is a multiple of 16)
+    uint4 *pq = (uint4 *)(L + c->wt.wqkv);
+    const int64_t KS = s.H / 32;
+    uint4 *pk = pq + (int64_t)(s.hq * d / 16) * KS * 64, *pv = pk + (int64_t)(s.hkv * d / 16) * KS * 64;
+    PAT_HIP(c, launch_pack_weight_qkv(wqkv + (int64_t)q0 * d * s.H, s.hq * d, s.H, s.H, s.hq * d, d, pq, c->stream));
+    PAT_HIP(c, launch_pack_weight_qkv(wqkv + ((int64_t)Hq + kv0) * d * s.H, s.hkv * d, s.H, s.H, s.hkv * d, d, pk, c->stream));
+    PAT_HIP(c, launch_pack_weight_qkv(wqkv + ((int64_t)Hq + Hkv + kv0) * d * s.H, s.hkv * d, s.H, s.H, 0, d, pv, c->stream));
+    // O and down take a column range (strided rows), gate and up a row range
+    PAT_HIP(c, launch_pack_weight(wo + (int64_t)q0 * d, nullptr, s.H, s.hq * d, (int64_t)Hq * d, (uint4 *)(L + c->wt.wo), c->stream));
+    PAT_HIP(c, launch_pack_weight(wg + (int64_t)f0 * s.H, wu + (int64_t)f0 * s.H, s.F, s.H, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
+    PAT_HIP(c, launch_pack_weight(wd + f0, nullptr, s.H, s.F, Ff, (uint4 *)(L + c->wt.wd), c->stream));
     c->layer_loaded[layer] = 1;
     return PAT_OK;
 }
@@ -360,7 +391,7 @@ int pat_load_final(pat_ctx *c, const pat_final_weights *w)
     char *Wb = at<char>(c->bufs.weights, 0);
     PAT_HIP(c, hipMemcpyAsync(Wb + c->wt.embed, w->embed, (size_t)s.V * s.H * 2, hipMemcpyDeviceToDevice, c->stream));
     PAT_HIP(c, hipMemcpyAsync(Wb + c->wt.gf, w->gf, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
-    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wlm, nullptr, s.Vs, s.H, (uint4 *)(Wb + c->wt.wlm), c->stream));
+    PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wlm, nullptr, s.Vs, s.H, s.H, (uint4 *)(Wb + c->wt.wlm), c->stream));
     c->final_loaded = true;
     return PAT_OK;
 }
@@ -757,7 +788,7 @@ int64_t pat_op_packed_act_bytes(int32_t b, int32_t k) { return (b <= 0 || k <= 0
 int pat_op_pack_weight(const void *w, const void *w2, int32_t n, int32_t k, void *packed, void *stream)
 {
     if (!w || !packed || n <= 0 || k <= 0 || k % 32) return PAT_EINVAL;
-    return launch_pack_weight((const uint16_t *)w, (const uint16_t *)w2, n, k, (uint4 *)packed, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+    return launch_pack_weight((const uint16_t *)w, (const uint16_t *)w2, n, k, k, (uint4 *)packed, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
 int pat_op_pack_act(const float *x, int32_t b, int32_t k, void *xhi, void *xlo, void *stream)

@@ -41,10 +41,11 @@ struct GemmPlan { int Kb, Rg, NB, MT, algo; };
 GemmPlan gemm_plan(int n_tiles, int KS, int B);
 void gemm_set_compute_units(int n);
 
-hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, uint4 *packed, hipStream_t s);
-// as above for a QKV matrix: within each of the first rope_rows / d heads, row p holds natural row
+// [n, k] (or gate/up pair w, w2) row-major with `ld` elements between rows -> streaming layout
+hipError_t launch_pack_weight(const uint16_t *w, const uint16_t *w2, int n, int k, int64_t ld, uint4 *packed, hipStream_t s);
+// as above for rows of a QKV matrix: within each of the first rope_rows / d heads, row p holds natural row
 // p/2 (p even) or p/2 + d/2 (p odd), so the two elements a rotation mixes are neighbours
-hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int rope_rows, int d, uint4 *packed, hipStream_t s);
+hipError_t launch_pack_weight_qkv(const uint16_t *w, int n, int k, int64_t ld, int rope_rows, int d, uint4 *packed, hipStream_t s);
 hipError_t launch_pack_act(const float *x, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);
 hipError_t launch_rmsnorm_pack(const float *x, const uint16_t *g, int b, int h, float eps, uint4 *hi, uint4 *lo,
                                hipStream_t s);

@@ -29,6 +29,7 @@ def main():
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--only", default="")
     ap.add_argument("--copy-gib", type=float, default=0.0)
+    ap.add_argument("--copies", type=int, default=6, help="distinct weight copies used in rotation (1 = cache-resident if it fits)")
     args = ap.parse_args()
     lib = pat.load_library()
     dev = "cuda:0"
@@ -47,7 +48,7 @@ def main():
         torch.cuda.synchronize()
         print(f"copy  {n} bytes read + {n} bytes written per launch", flush=True)
         del a, b
-    ncopy = 6
+    ncopy = max(1, args.copies)
     for name, (n, k, mode) in shapes.items():
         if only and name not in only:
             continue

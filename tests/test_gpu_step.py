@@ -399,3 +399,39 @@ def test_predictor_fitted_to_a_measured_grid_predicts_a_held_out_point():
     print(f"held-out B=4 L=1024: measured {held['mean_us']:.1f} us, predicted {p:.1f} us")
     assert abs(p / held["mean_us"] - 1.0) < 0.25
     dec.close()
+
+
+@pytest.mark.parametrize("hq,hkv,tp,rank", [(4, 4, 2, 1), (4, 4, 4, 3), (8, 2, 4, 2), (8, 2, 4, 1)])
+def test_weight_reslice_from_the_unsharded_layer_is_bitwise_the_shard(hq, hkv, tp, rank):
+    """Loading a rank's layer by slicing the unsharded tensors on the fly (weight re-slice after a TP
+    change) gives bit-for-bit the logits of loading the rank's own contiguous slices; the last two cases
+    have fewer KV heads than ranks (replicated KV heads)."""
+    m = pi.ModelShape(2, 256, hq, hkv, 64, 1024, 1024)
+    shard, full = pi.shard_of(m, tp, rank), pi.shard_of(m, 1, 0)
+    pat = _pat()
+    req = pi.rollout_requests(shard, 5, (20, 90), steps=3)
+    outs = []
+    for sliced in (False, True):
+        cfg = pat.make_cfg(shard, 8, 128, 1024, 16)
+        dec = pat.Decoder(cfg, DEV)
+        if sliced:
+            for l in range(m.n_layers):
+                dec.pat_load_layer_from_full(l, pi.layer_weights(full, l, device=DEV))
+                torch.cuda.synchronize()
+            fw = pi.final_weights(shard, device=DEV); fw["embed"] = pi.embedding_table(shard, device=DEV)
+            dec.pat_load_final(fw)
+            torch.cuda.synchronize()
+        else:
+            pat.load_synthetic_weights(dec, shard, DEV)
+        pat.admit_synthetic(dec, shard, req, DEV)
+        got = [_gpu_step(dec, 5, shard.vocab) for _ in range(2)]
+        outs.append(got)
+        dec.close()
+    for (la, na, _), (lb, nb, _) in zip(*outs):
+        assert np.array_equal(la.view(np.uint32), lb.view(np.uint32)) and np.array_equal(na, nb)
+    odec = make_oracle_decoder(shard)                                 # and the slices are the oracle's shard
+    oracle_admit(odec, shard, req, range(5), 3)
+    for la, na, _ in outs[1]:
+        ref_logits, ref_next, _ = odec.step()
+        check_logits(la, ref_logits)
+        assert np.array_equal(na, ref_next)
