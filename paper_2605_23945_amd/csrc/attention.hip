@@ -19,16 +19,6 @@ namespace {
 constexpr int kAttnThreads = 256;
 constexpr int kMaxChunk = 256;
 
-__device__ __forceinline__ int find_slot(const int32_t *chunk_start, int B, int ce)
-{
-    int lo = 0, hi = B;   // largest b with chunk_start[b] <= ce
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (chunk_start[mid] <= ce) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 template <int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
 {
@@ -49,12 +39,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
 
     for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
         const int ce = item / hkv, h = item - ce * hkv;
-        const int b = find_slot(a.chunk_start, a.B, ce);
-        const int c = ce - a.chunk_start[b];
-        const int n = a.kv_len[b] + 1;
-        const int t0 = c * C;
-        const int cnt = min(n - t0, C);
+        // one record per chunk (written by plan_step): slot, first token, token count, page ids
+        const int4 m0 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce];
+        const int4 m1 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce + 1];
+        const int b = m0.x, t0 = m0.y, cnt = m0.z;
+        const bool rec_pages = C <= 4 * P;            // the record holds every page of the chunk
         const int32_t *pt = a.page_table + (int64_t)b * a.max_pages;
+        const int pfirst = t0 / P;
         const int64_t head_off = (int64_t)h * P * D + seg * 8;
         // UR token rows per thread, requested together: page indices first (unconditional, clamped to
         // the chunk's last token), then the rows.  Conditional loads would serialise into
@@ -66,7 +57,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
                 const int tl = r0 + u * TPR + ts;
                 okk[u] = tl < cnt;
                 tc[u] = t0 + min(tl, cnt - 1);
-                page[u] = pt[tc[u] / P];
+                if (rec_pages) {
+                    const int j = tc[u] / P - pfirst;
+                    page[u] = j == 0 ? m1.x : j == 1 ? m1.y : j == 2 ? m1.z : m1.w;
+                } else {
+                    page[u] = pt[tc[u] / P];
+                }
             }
 #pragma unroll
             for (int u = 0; u < UR; ++u)

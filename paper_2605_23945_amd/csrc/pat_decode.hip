@@ -29,7 +29,7 @@ struct Shard {
 
 struct WorkLayout {   // byte offsets inside the work arena
     int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, sel, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
-    int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, tmp;
+    int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, chunk_meta, tmp;
     int64_t total;
     int64_t max_chunks;
 };
@@ -157,6 +157,7 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
 
     }
     w->max_chunks = c->kv_token_budget / kMinChunk + 2 * (int64_t)MB;
+    w->chunk_meta = take(w->max_chunks * 32);
     w->part_acc = take(w->max_chunks * s.hq * s.d * 4);
     w->part_ml = take(w->max_chunks * s.hq * 2 * 4);
     w->logits = take((int64_t)MB * s.Vs * 4);
@@ -301,7 +302,8 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
     c->st = StateArrays{at<int32_t>(W, w.seq_id), at<int32_t>(W, w.tok), at<int32_t>(W, w.kv_len), at<int32_t>(W, w.gen),
                         at<int32_t>(W, w.target), at<int32_t>(W, w.fin), at<int32_t>(W, w.page_table),
                         at<int32_t>(W, w.page_table_tmp), at<int32_t>(W, w.free_stack), at<int32_t>(W, w.scalars),
-                        at<int32_t>(W, w.chunk_start), at<int32_t>(W, w.tmp), s.max_pages, cfg->page_tokens};
+                        at<int32_t>(W, w.chunk_start), at<int32_t>(W, w.chunk_meta), (int)std::min<int64_t>(w.max_chunks, INT32_MAX),
+                        at<int32_t>(W, w.tmp), s.max_pages, cfg->page_tokens};
     c->layer_loaded.assign(s.NL, 0);
     const int MB = cfg->max_batch;
     c->seq_id.resize(MB); c->kv_len.resize(MB); c->gen.resize(MB); c->target.resize(MB); c->fin.assign(MB, 0);
@@ -556,7 +558,7 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
 
     AttnArgs aa{};
     aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = c->st.kv_len;
-    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_tokens = C;
+    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_meta = c->st.chunk_meta; aa.chunk_tokens = C;
     aa.part_acc = at<float>(W, w.part_acc); aa.part_ml = at<float>(W, w.part_ml); aa.ohi = b_hi; aa.olo = b_lo;
     aa.n_items = (int)(n_chunks * s.hkv);
 

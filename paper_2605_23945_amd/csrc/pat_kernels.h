@@ -62,6 +62,7 @@ struct AttnArgs {
     const int32_t *page_table; // [max_batch][max_pages]
     int max_pages;
     const int32_t *chunk_start;// [B + 1] exclusive prefix of per-slot chunk counts
+    const int32_t *chunk_meta; // [n_chunks_total][8] written by plan_step (see StateArrays)
     int chunk_tokens;
     float *part_acc;           // [n_chunks_total][hq][d]
     float *part_ml;            // [n_chunks_total][hq][2]  (max, sum)
@@ -79,6 +80,8 @@ struct StateArrays {           // device int32 arrays of max_batch entries
     int32_t *free_stack;       // [n_pages]
     int32_t *scalars;          // [0] n_free, [1] live, [2] n_finished, [3] chunks_total, [4..5] sum_ctx (int64), [6] step, [7] error
     int32_t *chunk_start;      // [max_batch + 1]
+    int32_t *chunk_meta;       // [max_chunks][8]: slot, first token, tokens, -, then the chunk's first 4 page ids
+    int max_chunks;
     int32_t *tmp;              // [8 * max_batch] scratch for compaction
     int max_pages, P;
 };

@@ -63,9 +63,13 @@ __global__ __launch_bounds__(kBlk) void admit_kernel(StateArrays st, int live, i
 }
 
 // Before a step: per-slot chunk counts -> exclusive prefix; a fresh page for
-// every slot whose next token starts a new page.
+// every slot whose next token starts a new page; then one record per attention chunk
+// (slot, first token, token count, its first four page ids), so that an attention
+// workgroup learns all it needs from a single 32-byte load instead of a search through the
+// prefix followed by length and page-table lookups.
 __global__ __launch_bounds__(kBlk) void plan_step_kernel(StateArrays st, int B, int C)
 {
+    __shared__ int s_start[kBlk + 1];
     const int i = threadIdx.x;
     const int L = (i < B) ? st.kv_len[i] : 0;
     const int chunks = (i < B) ? (L + 1 + C - 1) / C : 0;
@@ -73,13 +77,27 @@ __global__ __launch_bounds__(kBlk) void plan_step_kernel(StateArrays st, int B, 
     int tot_c, tot_p;
     const int off_c = block_exclusive_scan(chunks, tot_c);
     const int off_p = block_exclusive_scan(need, tot_p);
-    if (i < B) st.chunk_start[i] = off_c;
-    if (i == 0) { st.chunk_start[B] = tot_c; st.scalars[S_CHUNKS] = tot_c; }
+    if (i < B) { st.chunk_start[i] = off_c; s_start[i] = off_c; }
+    if (i == 0) { st.chunk_start[B] = tot_c; st.scalars[S_CHUNKS] = tot_c; s_start[B] = tot_c; }
     const int n_free = st.scalars[S_NFREE];
     if (tot_p > n_free) { if (i == 0) st.scalars[S_ERR] = 2; return; }
     if (need) st.page_table[(int64_t)i * st.max_pages + L / st.P] = st.free_stack[n_free - 1 - off_p];
-    __syncthreads();
+    __syncthreads();                                   // page-table rows and s_start are complete
     if (i == 0) st.scalars[S_NFREE] = n_free - tot_p;
+    const int n_rec = min(tot_c, st.max_chunks);       // the host checked the count against the workspace
+    for (int ce = i; ce < n_rec; ce += kBlk) {
+        int lo = 0, hi = B;                            // largest b with s_start[b] <= ce
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_start[mid] <= ce) lo = mid; else hi = mid; }
+        const int b = lo, t0 = (ce - s_start[b]) * C;
+        const int n = st.kv_len[b] + 1;
+        const int cnt = min(n - t0, C);
+        const int32_t *pt = st.page_table + (int64_t)b * st.max_pages;
+        const int p0 = t0 / st.P, plast = (t0 + cnt - 1) / st.P;
+        int4 m0 = make_int4(b, t0, cnt, 0), m1;
+        m1.x = pt[p0]; m1.y = pt[min(p0 + 1, plast)]; m1.z = pt[min(p0 + 2, plast)]; m1.w = pt[min(p0 + 3, plast)];
+        reinterpret_cast<int4 *>(st.chunk_meta)[2 * (int64_t)ce] = m0;
+        reinterpret_cast<int4 *>(st.chunk_meta)[2 * (int64_t)ce + 1] = m1;
+    }
 }
 
 __global__ void embed_kernel(const uint16_t *table, int H, const int32_t *tok, float *x)
