@@ -70,14 +70,17 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
             __builtin_amdgcn_sched_barrier(0);
         };
 
-        float q[G][8];
+        constexpr bool kMatrixQK = G >= 4;      // scores on the matrix cores when several query heads share the KV head
+        float q[kMatrixQK ? 1 : G][8];
+        if (!kMatrixQK) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + g) * D + seg * 8;
-            const float4 q0 = *reinterpret_cast<const float4 *>(qp);
-            const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
-            q[g][0] = q0.x; q[g][1] = q0.y; q[g][2] = q0.z; q[g][3] = q0.w;
-            q[g][4] = q1.x; q[g][5] = q1.y; q[g][6] = q1.z; q[g][7] = q1.w;
+            for (int g = 0; g < G; ++g) {
+                const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + g) * D + seg * 8;
+                const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+                const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+                q[g][0] = q0.x; q[g][1] = q0.y; q[g][2] = q0.z; q[g][3] = q0.w;
+                q[g][4] = q1.x; q[g][5] = q1.y; q[g][6] = q1.z; q[g][7] = q1.w;
+            }
         }
 
         // The first batch of V rows is requested together with the K rows: a short chunk then
@@ -87,6 +90,68 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         load_rows(vbase, 0, vfirst, okv);
 
         // ---- scores of the chunk ----
+        if (kMatrixQK) {
+            // S[query head, token] = Q K^T as 16 x 16 x 32 matrix products: the A operand holds the G
+            // query heads of this KV head as rows (rows G..15 are zero), split into two bf16 terms so
+            // that the products keep fp32-class accuracy; the B operand is 16 token rows of K, each
+            // lane taking 8 consecutive features of its token straight from the page (no LDS).
+            // A wave scores 16 tokens per product group, the workgroup 64, two groups in flight.
+            constexpr int KST = D / 32, UM = 2;
+            const int row = lane & 15, dg = lane >> 4;
+            u32x4_t qh[KST], ql[KST];
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) {
+                const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + min(row, G - 1)) * D + ks * 32 + dg * 8;
+                const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+                const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+                const float qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+                uint16_t hh[8], ll[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) split_bf16(row < G ? qv[j] : 0.f, hh[j], ll[j]);
+                qh[ks] = u32x4_t{(uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16),
+                                 (uint32_t)hh[4] | ((uint32_t)hh[5] << 16), (uint32_t)hh[6] | ((uint32_t)hh[7] << 16)};
+                ql[ks] = u32x4_t{(uint32_t)ll[0] | ((uint32_t)ll[1] << 16), (uint32_t)ll[2] | ((uint32_t)ll[3] << 16),
+                                 (uint32_t)ll[4] | ((uint32_t)ll[5] << 16), (uint32_t)ll[6] | ((uint32_t)ll[7] << 16)};
+            }
+            const int64_t khead = (int64_t)h * P * D + dg * 8;
+            for (int r0 = 0; r0 < cnt; r0 += 64 * UM) {
+                u32x4_t kf[UM][KST];
+                int tl[UM];
+#pragma unroll
+                for (int u = 0; u < UM; ++u) {
+                    tl[u] = r0 + u * 64 + wave * 16 + row;
+                    const int tc = t0 + min(tl[u], cnt - 1);
+                    int page;
+                    if (rec_pages) {
+                        const int j = tc / P - pfirst;
+                        page = j == 0 ? m1.x : j == 1 ? m1.y : j == 2 ? m1.z : m1.w;
+                    } else {
+                        page = pt[tc / P];
+                    }
+                    const uint16_t *kr = kbase + page * page_elems + khead + (int64_t)(tc % P) * D;
+#pragma unroll
+                    for (int ks = 0; ks < KST; ++ks) kf[u][ks] = *reinterpret_cast<const u32x4_t *>(kr + ks * 32);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < UM; ++u) {
+                    floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KST; ++ks) {
+                        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qh[ks]), __builtin_bit_cast(bf16x8_t, kf[u][ks]), sacc, 0, 0, 0);
+                        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ql[ks]), __builtin_bit_cast(bf16x8_t, kf[u][ks]), sacc, 0, 0, 0);
+                    }
+                    // result tile: this lane holds query heads (lane / 16) * 4 .. + 3 of token column lane % 16
+                    if (tl[u] < cnt) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int g = dg * 4 + j;
+                            if (g < G) sc[g * kMaxChunk + tl[u]] = sacc[j] * scale;
+                        }
+                    }
+                }
+            }
+        } else {
         for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
             uint4 kv[UR];
             bool ok[UR];
@@ -106,6 +171,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
                     if (seg == 0 && ok[u]) sc[g * kMaxChunk + r0 + u * TPR + ts] = s * scale;
                 }
             }
+        }
         }
         __syncthreads();
 

@@ -38,7 +38,6 @@ __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c)
 // Native vector flavour of a 16-byte fragment.  Values that are loaded in one loop iteration and
 // used in a later one are held in this type: assignments of the runtime's uint4 class can be
 // lowered to memcpy between address spaces, which pins the variable in scratch memory.
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ u32x4_t ld16(const uint4 *p) { return *reinterpret_cast<const u32x4_t *>(p); }
 __device__ __forceinline__ void st16(uint4 *p, u32x4_t v) { *reinterpret_cast<u32x4_t *>(p) = v; }
 __device__ __forceinline__ floatx4_t mfma16(u32x4_t a, uint4 b, floatx4_t c)

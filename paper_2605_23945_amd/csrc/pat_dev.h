@@ -7,6 +7,7 @@ namespace pat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));     // a 16-byte fragment as a native vector
 
 constexpr int kWave = 64;
 
