@@ -463,11 +463,31 @@ __global__ void pack_act_kernel(const float *x, int b, int k, int KS, uint4 *hi,
 __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const uint16_t *g, int h, int KS,
                                                            float eps, uint4 *hi, uint4 *lo)
 {
+    // The row is read once: up to kKeep x 2048 features stay in registers between the sum of squares
+    // and the scaling (the rest, for wider models, is read again), and the gains are requested with it.
+    constexpr int kKeep = 4;
     __shared__ float part[4];
     const int row = blockIdx.x;
     const float *xr = x + (int64_t)row * h;
+    float4 xp[kKeep], xq[kKeep];
+    uint4 gk[kKeep];
     float ss = 0.f;
-    for (int k0 = threadIdx.x * 8; k0 < h; k0 += 256 * 8) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        const int k0 = threadIdx.x * 8 + i * 2048;
+        const int kc = min(k0, h - 8);                        // past the row: a clamped, unused load
+        xp[i] = *reinterpret_cast<const float4 *>(xr + kc);
+        xq[i] = *reinterpret_cast<const float4 *>(xr + kc + 4);
+        gk[i] = *reinterpret_cast<const uint4 *>(g + kc);
+    }
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        if (threadIdx.x * 8 + i * 2048 < h) {
+            const float4 p = xp[i], q = xq[i];
+            ss += p.x * p.x + p.y * p.y + p.z * p.z + p.w * p.w + q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
+        }
+    }
+    for (int k0 = threadIdx.x * 8 + kKeep * 2048; k0 < h; k0 += 2048) {
         const float4 p = *reinterpret_cast<const float4 *>(xr + k0);
         const float4 q = *reinterpret_cast<const float4 *>(xr + k0 + 4);
         ss += p.x * p.x + p.y * p.y + p.z * p.z + p.w * p.w + q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
@@ -477,10 +497,7 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const
     __syncthreads();
     const float tot = (part[0] + part[1]) + (part[2] + part[3]);
     const float inv = 1.0f / sqrtf(tot / (float)h + eps);
-    for (int k0 = threadIdx.x * 8; k0 < h; k0 += 256 * 8) {
-        const float4 p = *reinterpret_cast<const float4 *>(xr + k0);
-        const float4 q = *reinterpret_cast<const float4 *>(xr + k0 + 4);
-        const uint4 gv = *reinterpret_cast<const uint4 *>(g + k0);
+    auto emit = [&](int k0, float4 p, float4 q, uint4 gv) {
         const float v[8] = {p.x * inv * bf16lo(gv.x), p.y * inv * bf16hi(gv.x), p.z * inv * bf16lo(gv.y),
                             p.w * inv * bf16hi(gv.y), q.x * inv * bf16lo(gv.z), q.y * inv * bf16hi(gv.z),
                             q.z * inv * bf16lo(gv.w), q.w * inv * bf16hi(gv.w)};
@@ -492,7 +509,15 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const
                             hh[6] | (uint32_t)hh[7] << 16);
         lo[vi] = make_uint4(ll[0] | (uint32_t)ll[1] << 16, ll[2] | (uint32_t)ll[3] << 16, ll[4] | (uint32_t)ll[5] << 16,
                             ll[6] | (uint32_t)ll[7] << 16);
+    };
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        const int k0 = threadIdx.x * 8 + i * 2048;
+        if (k0 < h) emit(k0, xp[i], xq[i], gk[i]);
     }
+    for (int k0 = threadIdx.x * 8 + kKeep * 2048; k0 < h; k0 += 2048)
+        emit(k0, *reinterpret_cast<const float4 *>(xr + k0), *reinterpret_cast<const float4 *>(xr + k0 + 4),
+             *reinterpret_cast<const uint4 *>(g + k0));
 }
 
 template <int NB, int UK, int TB, int kXsWaves>

@@ -103,7 +103,7 @@ def test_pack_act_split_is_fp32_class(pat):
     assert rel.max() <= 2.0 ** -16
 
 
-@pytest.mark.parametrize("b,h", [(1, 256), (7, 4096), (20, 5120)])
+@pytest.mark.parametrize("b,h", [(1, 256), (7, 4096), (20, 5120), (3, 10240), (2, 8192)])
 def test_rmsnorm_pack_vs_oracle(pat, orc, b, h):
     x = _x(b, h, 17) * 3.0
     g = pi.normal_bf16(pi.stream_key(1, 2), torch.arange(h, dtype=torch.int64), 0.02, 1.0)
