@@ -59,7 +59,9 @@ def test_weight_packing_and_mfma_layout_exact(pat):
                                    (64, 256, 100), (48, 64, 256), (4096, 4096, 8), (16, 32, 3),
                                    (4096, 1024, 200), (528, 2752, 130), (1024, 4096, 40), (256, 8192, 30),
                                    (4096, 4096, 256), (2048, 11008, 96), (8192, 512, 192), (16384, 1024, 255),
-                                   (34000, 512, 250), (4112, 1024, 65), (22016, 1024, 129)])
+                                   (34000, 512, 250), (4112, 1024, 65), (22016, 1024, 129),
+                                   (4096, 4096, 1), (4096, 11008, 2), (1040, 352, 2), (2064, 4096, 2), (16, 32, 1), (48, 64, 2),
+                                   (8192, 28672, 1)])
 def test_gemm_store_and_accumulate_vs_oracle(pat, orc, n, k, b):
     w, x = _w(n, k, 2 + n + k), _x(b, k, n + b)
     wp = pat.pat_op_pack_weight(w.to(DEV))
@@ -79,7 +81,7 @@ def test_gemm_store_and_accumulate_vs_oracle(pat, orc, n, k, b):
 
 
 @pytest.mark.parametrize("f,k,b", [(64, 256, 3), (352, 512, 16), (1024, 256, 40), (512, 2048, 70), (64, 4096, 9),
-                                   (2752, 1024, 256), (1376, 4096, 150)])
+                                   (2752, 1024, 256), (1376, 4096, 150), (352, 512, 2), (64, 4096, 1)])
 def test_gemm_swiglu_epilogue_vs_oracle(pat, orc, f, k, b):
     wg, wu, x = _w(f, k, 11, 0.05), _w(f, k, 12, 0.05), _x(b, k, 5)
     wp = pat.pat_op_pack_weight(wg.to(DEV), wu.to(DEV))
