@@ -129,9 +129,13 @@ class Oracle:
         g1, g1p = self._b(w["g1"]); wqkv, wqp = self._b(w["wqkv"]); wo, wop = self._b(w["wo"])
         assert wqkv.shape == ((hq + 2 * hkv) * d, H) and wo.shape == (H, hq * d)
         delta = np.empty(H, self.real)
-        self.lib.orc_attn_sublayer(C.c_int(H), C.c_int(hq), C.c_int(hkv), C.c_int(d), C.c_double(eps),
-                                   C.c_double(base), g1p, wqp, wop, xp, _p(kc, _u16p), _p(vc, _u16p),
-                                   C.c_int(L), _p(delta, self._rp))
+        gq = gk = None
+        if "gq" in w:                                    # model family with per-head q/k normalisation
+            (gqa, gq), (gka, gk) = self._b(w["gq"]), self._b(w["gk"])
+            assert gqa.shape == (d,) and gka.shape == (d,)
+        self.lib.orc_attn_sublayer_qkn(C.c_int(H), C.c_int(hq), C.c_int(hkv), C.c_int(d), C.c_double(eps),
+                                       C.c_double(base), g1p, wqp, wop, gq, gk, xp, _p(kc, _u16p), _p(vc, _u16p),
+                                       C.c_int(L), _p(delta, self._rp))
         return delta
 
     def ffn_sublayer(self, H, F, eps, w, x):
@@ -150,9 +154,13 @@ class Oracle:
         g1, g1p = self._b(w["g1"]); wqkv, wqp = self._b(w["wqkv"]); wo, wop = self._b(w["wo"])
         g2, g2p = self._b(w["g2"]); wg, wgp = self._b(w["wg"]); wu, wup = self._b(w["wu"]); wd, wdp = self._b(w["wd"])
         assert kc.flags.c_contiguous and vc.flags.c_contiguous and kc.shape[0] > L
-        self.lib.orc_layer(C.c_int(H), C.c_int(hq), C.c_int(hkv), C.c_int(d), C.c_int(F), C.c_double(eps),
-                           C.c_double(base), g1p, wqp, wop, g2p, wgp, wup, wdp, _p(x, self._rp),
-                           _p(kc, _u16p), _p(vc, _u16p), C.c_int(L))
+        gq = gk = None
+        if "gq" in w:                                    # model family with per-head q/k normalisation
+            (gqa, gq), (gka, gk) = self._b(w["gq"]), self._b(w["gk"])
+            assert gqa.shape == (d,) and gka.shape == (d,)
+        self.lib.orc_layer_qkn(C.c_int(H), C.c_int(hq), C.c_int(hkv), C.c_int(d), C.c_int(F), C.c_double(eps),
+                               C.c_double(base), g1p, wqp, wop, g2p, wgp, wup, wdp, gq, gk, _p(x, self._rp),
+                               _p(kc, _u16p), _p(vc, _u16p), C.c_int(L))
 
     def logits(self, H, eps, w, x):
         x, xp = self._r(x)

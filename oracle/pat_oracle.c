@@ -160,16 +160,22 @@ real orc_silu(real z) { return z / ((real)1 + (real)exp(-(double)z)); }
  * Appends the new token's k, v at index L (so cap > L) and writes
  *   delta = attention(x) Wo^T   (this shard's partial, residual not added).
  */
-void orc_attn_sublayer(int H, int hq, int hkv, int d, double eps, double rope_base,
-                       const uint16_t *g1, const uint16_t *wqkv, const uint16_t *wo,
-                       const real *x, uint16_t *Kc, uint16_t *Vc, int L, real *delta)
+void orc_attn_sublayer_qkn(int H, int hq, int hkv, int d, double eps, double rope_base,
+                           const uint16_t *g1, const uint16_t *wqkv, const uint16_t *wo,
+                           const uint16_t *gq, const uint16_t *gk,
+                           const real *x, uint16_t *Kc, uint16_t *Vc, int L, real *delta)
 {
     int nq = hq * d, nkv = hkv * d, rows = nq + 2 * nkv;
     real *h = malloc(sizeof(real) * H), *qkv = malloc(sizeof(real) * rows);
     real *o = malloc(sizeof(real) * nq), *p = malloc(sizeof(real) * (L + 1));
+    real *t = malloc(sizeof(real) * d);
     orc_rmsnorm(x, g1, H, eps, h);
     orc_matvec(wqkv, rows, H, H, h, qkv);
     real *q = qkv, *k = qkv + nq, *v = qkv + nq + nkv;
+    /* model family with per-head query/key normalisation: every q head and k head is RMS-normalised
+     * over its d features with gains gq / gk (shared by the heads) before the rotary embedding */
+    if (gq) for (int a = 0; a < hq; ++a) { orc_rmsnorm(q + a * d, gq, d, eps, t); for (int e = 0; e < d; ++e) q[a * d + e] = t[e]; }
+    if (gk) for (int a = 0; a < hkv; ++a) { orc_rmsnorm(k + a * d, gk, d, eps, t); for (int e = 0; e < d; ++e) k[a * d + e] = t[e]; }
     for (int a = 0; a < hq; ++a) orc_rope(q + a * d, d, L, rope_base);
     for (int a = 0; a < hkv; ++a) orc_rope(k + a * d, d, L, rope_base);
     for (int e = 0; e < nkv; ++e) {
@@ -182,7 +188,14 @@ void orc_attn_sublayer(int H, int hq, int hkv, int d, double eps, double rope_ba
         orc_attend(q + a * d, Kc + kvh * d, Vc + kvh * d, L + 1, nkv, d, o + a * d, p);
     }
     orc_matvec(wo, H, nq, nq, o, delta);
-    free(h); free(qkv); free(o); free(p);
+    free(h); free(qkv); free(o); free(p); free(t);
+}
+
+void orc_attn_sublayer(int H, int hq, int hkv, int d, double eps, double rope_base,
+                       const uint16_t *g1, const uint16_t *wqkv, const uint16_t *wo,
+                       const real *x, uint16_t *Kc, uint16_t *Vc, int L, real *delta)
+{
+    orc_attn_sublayer_qkn(H, hq, hkv, d, eps, rope_base, g1, wqkv, wo, NULL, NULL, x, Kc, Vc, L, delta);
 }
 
 /* SwiGLU sub-layer: delta = (silu(h Wg^T) * (h Wu^T)) Wd^T with h = RMSNorm(x; g2);
@@ -199,18 +212,28 @@ void orc_ffn_sublayer(int H, int F, double eps, const uint16_t *g2, const uint16
     free(h); free(g); free(u);
 }
 
-/* One whole layer in place: x += attention partial; x += FFN partial. */
+/* One whole layer in place: x += attention partial; x += FFN partial.  gq, gk: per-head q/k
+ * normalisation gains, or NULL for the model family without it. */
+void orc_layer_qkn(int H, int hq, int hkv, int d, int F, double eps, double rope_base,
+                   const uint16_t *g1, const uint16_t *wqkv, const uint16_t *wo,
+                   const uint16_t *g2, const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
+                   const uint16_t *gq, const uint16_t *gk,
+                   real *x, uint16_t *Kc, uint16_t *Vc, int L)
+{
+    real *delta = malloc(sizeof(real) * H);
+    orc_attn_sublayer_qkn(H, hq, hkv, d, eps, rope_base, g1, wqkv, wo, gq, gk, x, Kc, Vc, L, delta);
+    for (int k = 0; k < H; ++k) x[k] += delta[k];
+    orc_ffn_sublayer(H, F, eps, g2, wg, wu, wd, x, delta);
+    for (int k = 0; k < H; ++k) x[k] += delta[k];
+    free(delta);
+}
+
 void orc_layer(int H, int hq, int hkv, int d, int F, double eps, double rope_base,
                const uint16_t *g1, const uint16_t *wqkv, const uint16_t *wo,
                const uint16_t *g2, const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
                real *x, uint16_t *Kc, uint16_t *Vc, int L)
 {
-    real *delta = malloc(sizeof(real) * H);
-    orc_attn_sublayer(H, hq, hkv, d, eps, rope_base, g1, wqkv, wo, x, Kc, Vc, L, delta);
-    for (int k = 0; k < H; ++k) x[k] += delta[k];
-    orc_ffn_sublayer(H, F, eps, g2, wg, wu, wd, x, delta);
-    for (int k = 0; k < H; ++k) x[k] += delta[k];
-    free(delta);
+    orc_layer_qkn(H, hq, hkv, d, F, eps, rope_base, g1, wqkv, wo, g2, wg, wu, wd, NULL, NULL, x, Kc, Vc, L);
 }
 
 /* logits over this shard's vocabulary rows: RMSNorm(x; gf) Wlm^T. */

@@ -25,7 +25,7 @@ SEED_KV = 0x5EED0002
 SEED_TOKENS = 0x5EED0003
 
 # tensor kinds inside one layer's stream id
-_G1, _WQ, _WK, _WV, _WO, _G2, _WG, _WU, _WD, _WLM, _EMB = range(1, 12)
+_G1, _WQ, _WK, _WV, _WO, _G2, _WG, _WU, _WD, _WLM, _EMB, _GQ, _GK = range(1, 14)
 
 
 @dataclass(frozen=True)
@@ -39,6 +39,7 @@ class ModelShape:
     vocab: int
     rms_eps: float = 1e-6
     rope_base: float = 10000.0
+    qk_norm: bool = False      # per-head RMSNorm of q and k before the rotary embedding (gains gq, gk [head_dim])
 
 
 @dataclass(frozen=True)
@@ -132,7 +133,7 @@ def embedding_rows(s: ShardShape, tokens, device="cpu", seed=SEED_WEIGHTS) -> to
 def layer_weights(s: ShardShape, layer: int, device="cpu", seed=SEED_WEIGHTS) -> dict:
     """Shard `s`'s tensors of one layer, row-major bf16:
 
-    g1, g2 [H]; wqkv [(hq + 2 hkv) d, H] (q rows, then k rows, then v rows of this
+    g1, g2 [H] (and gq, gk [d] if the model normalises q and k per head); wqkv [(hq + 2 hkv) d, H] (q rows, then k rows, then v rows of this
     shard's heads); wo [H, hq d] (this shard's columns); wg, wu [F_s, H];
     wd [H, F_s] (this shard's columns).
     """
@@ -142,7 +143,11 @@ def layer_weights(s: ShardShape, layer: int, device="cpu", seed=SEED_WEIGHTS) ->
     wq = _rows(k(_WQ), q0, q0 + s.hq * d, H, 0.02, 0.0, device)
     wk = _rows(k(_WK), kv0, kv0 + s.hkv * d, H, 0.02, 0.0, device)
     wv = _rows(k(_WV), kv0, kv0 + s.hkv * d, H, 0.02, 0.0, device)
+    extra = {}
+    if m.qk_norm:                      # shared by all heads, hence by all shards
+        extra = dict(gq=_rows(k(_GQ), 0, 1, d, 0.02, 1.0, device).view(d), gk=_rows(k(_GK), 0, 1, d, 0.02, 1.0, device).view(d))
     return dict(
+        **extra,
         g1=_rows(k(_G1), 0, 1, H, 0.02, 1.0, device).view(H),
         g2=_rows(k(_G2), 0, 1, H, 0.02, 1.0, device).view(H),
         wqkv=torch.cat([wq, wk, wv], 0).contiguous(),

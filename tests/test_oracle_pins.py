@@ -193,8 +193,12 @@ def _torch_attn_sublayer(H, hq, hkv, d, eps, base, w, x, kc, vc, L):
     x = torch.from_numpy(x)
     h = F.rms_norm(x, (H,), _w64(w["g1"]), eps=eps)
     qkv = _w64(w["wqkv"]) @ h
-    q = _torch_rope(qkv[: hq * d].view(hq, d), L, base)
-    k = _torch_rope(qkv[hq * d:(hq + hkv) * d].view(hkv, d), L, base)
+    q, k = qkv[: hq * d].view(hq, d), qkv[hq * d:(hq + hkv) * d].view(hkv, d)
+    if "gq" in w:                                            # per-head normalisation before the rotation
+        q = F.rms_norm(q, (d,), _w64(w["gq"]), eps=eps)
+        k = F.rms_norm(k, (d,), _w64(w["gk"]), eps=eps)
+    q = _torch_rope(q, L, base)
+    k = _torch_rope(k, L, base)
     v = qkv[(hq + hkv) * d:].view(hkv, d)
     kb = bits(k.to(torch.float32).to(torch.bfloat16)); vb = bits(v.to(torch.float32).to(torch.bfloat16))
     K = torch.cat([_w64(kc[:L]), _w64(kb)[None]], 0)       # [L+1, hkv, d]
@@ -217,6 +221,32 @@ def test_attn_sublayer_vs_library_composition(orc, hq, hkv):
     np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
     # the appended entries are the bf16 roundings of k (rotated at position L) and v
     assert np.array_equal(kc[L], kb) and np.array_equal(vc[L], vb)
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2)])
+def test_attn_sublayer_with_per_head_qk_norm_vs_library_composition(orc, hq, hkv):
+    H, d, L, eps, base = 64, 16, 13, 1e-6, 10000.0
+    w = dict(g1=bf16_bits_of(1 + 0.02 * RNG.standard_normal(H).astype(np.float32)),
+             wqkv=rand_bf16(((hq + 2 * hkv) * d, H), 0.05), wo=rand_bf16((H, hq * d), 0.05),
+             gq=bf16_bits_of(1 + 0.3 * RNG.standard_normal(d).astype(np.float32)),
+             gk=bf16_bits_of(1 + 0.3 * RNG.standard_normal(d).astype(np.float32)))
+    x = RNG.standard_normal(H)
+    kc = np.zeros((L + 1, hkv, d), np.uint16); vc = np.zeros((L + 1, hkv, d), np.uint16)
+    kc[:L] = rand_bf16((L, hkv, d)); vc[:L] = rand_bf16((L, hkv, d))
+    kc2, vc2 = kc.copy(), vc.copy()
+    ref, kb, vb = _torch_attn_sublayer(H, hq, hkv, d, eps, base, w, x, kc, vc, L)
+    got = orc.attn_sublayer((H, hq, hkv, d, eps, base), w, x, kc, vc, L)
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+    assert np.array_equal(kc[L], kb) and np.array_equal(vc[L], vb)
+    # the normalisation matters (it is not a no-op on these inputs) and leaves v alone
+    plain = orc.attn_sublayer((H, hq, hkv, d, eps, base), {k: v for k, v in w.items() if k not in ("gq", "gk")}, x, kc2, vc2, L)
+    assert np.max(np.abs(plain - got)) > 1e-3 * np.max(np.abs(got))
+    assert np.array_equal(vc2[L], vc[L]) and not np.array_equal(kc2[L], kc[L])
+    # scale invariance: a normalised k does not change when the k rows of the projection are scaled
+    w2 = dict(w); wq2 = widen(w["wqkv"]).astype(np.float32).copy(); wq2[hq * d:(hq + hkv) * d] *= 2.0; w2["wqkv"] = bf16_bits_of(wq2)
+    kc3, vc3 = kc2.copy(), vc2.copy()
+    got2 = orc.attn_sublayer((H, hq, hkv, d, eps, base), w2, x, kc3, vc3, L)
+    np.testing.assert_allclose(got2, got, rtol=1e-6, atol=1e-9)
 
 
 def test_ffn_sublayer_vs_library_composition(orc):
