@@ -61,6 +61,7 @@ def main():
                 sum(running_need) + sum(int(need[i]) for i in batch) + int(need[waiting[0]]) <= budget:
             batch.append(waiting.pop(0))
         if batch:
+            print(f"admitting {len(batch)} requests", file=sys.stderr, flush=True)
             pat.admit_synthetic(dec, shard, req, dev, idx=batch)
             running_need.extend(int(need[i]) for i in batch)
             target_left.extend(int(req["target"][i]) for i in batch)
@@ -96,6 +97,7 @@ def main():
         if len(pending) >= 512:
             torch.cuda.synchronize()
             ms += [x.elapsed_time(y) for x, y in pending]; pending.clear()
+            print(f"step {steps}: live {len(running_need)}, waiting {len(waiting)}, {sum(ms) * 1e-3:.1f} s in steps", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     ms += [x.elapsed_time(y) for x, y in pending]
     ms = np.array(ms); lives = np.array(lives); byt = np.array(wbytes) + np.array(kvbytes)
