@@ -53,6 +53,8 @@ typedef struct pat_cfg {
     int32_t page_tokens;      /* tokens per KV page */
     int64_t kv_token_budget;  /* active-token capacity of the KV pool: the paper's T_cap (Sec. 4.1) */
     int32_t eos_token;        /* < 0: sequences end by target length only */
+    int32_t qk_norm;          /* != 0: model family with per-head RMSNorm of q and k (gains gq, gk, same
+                                 epsilon) before the rotary embedding, e.g. the paper's second model */
 } pat_cfg;
 
 /* Arena sizes in bytes for a configuration. */
@@ -70,9 +72,11 @@ typedef struct pat_buffers {  /* device arenas, 256-byte aligned, sizes from pat
 
 /* One layer of this shard, device, row-major bf16:
  *   g1, g2 [hidden]; wqkv [(hq + 2 hkv) d, hidden] (q rows, k rows, v rows);
- *   wo [hidden, hq d]; wg, wu [F, hidden]; wd [hidden, F].                      */
+ *   wo [hidden, hq d]; wg, wu [F, hidden]; wd [hidden, F];
+ *   gq, gk [head_dim]: only read when cfg.qk_norm is set (else may be NULL).   */
 typedef struct pat_layer_weights {
     const void *g1, *wqkv, *wo, *g2, *wg, *wu, *wd;
+    const void *gq, *gk;
 } pat_layer_weights;
 
 /* embed [vocab, hidden] (full table, replicated); gf [hidden]; wlm [Vs, hidden]. */

@@ -28,7 +28,7 @@ class pat_cfg(C.Structure):
                                          "tp_degree", "tp_rank")] + \
                [("rms_eps", C.c_float), ("rope_base", C.c_float),
                 ("max_batch", C.c_int32), ("max_seq_len", C.c_int32), ("page_tokens", C.c_int32),
-                ("kv_token_budget", C.c_int64), ("eos_token", C.c_int32)]
+                ("kv_token_budget", C.c_int64), ("eos_token", C.c_int32), ("qk_norm", C.c_int32)]
 
 
 class pat_mem_req(C.Structure):
@@ -41,7 +41,7 @@ class pat_buffers(C.Structure):
 
 
 class pat_layer_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")]
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd", "gq", "gk")]
 
 
 class pat_final_weights(C.Structure):
@@ -153,7 +153,8 @@ def make_cfg(shard, max_batch, max_seq_len, kv_token_budget, page_tokens=64, eos
     """pat_cfg from a pat_inputs.ShardShape-like object (fields model.*, tp, rank)."""
     m = shard.model
     return pat_cfg(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, shard.tp, shard.rank,
-                   m.rms_eps, m.rope_base, max_batch, max_seq_len, page_tokens, kv_token_budget, eos_token)
+                   m.rms_eps, m.rope_base, max_batch, max_seq_len, page_tokens, kv_token_budget, eos_token,
+                   1 if getattr(m, "qk_norm", False) else 0)
 
 
 def _i32(a):
@@ -212,12 +213,12 @@ class Decoder:
 
     # -- same names as the C ABI ---------------------------------------------------
     def pat_load_layer(self, layer, w: dict):
-        lw = pat_layer_weights(*[_ptr(w[k]) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")])
+        lw = pat_layer_weights(*[_ptr(w.get(k)) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd", "gq", "gk")])
         self._chk(self.lib.pat_load_layer(self.ctx, layer, C.byref(lw)))
 
     def pat_load_layer_from_full(self, layer, w: dict):
         """w: the UNSHARDED layer's tensors (same keys as pat_load_layer)."""
-        lw = pat_layer_weights(*[_ptr(w[k]) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd")])
+        lw = pat_layer_weights(*[_ptr(w.get(k)) for k in ("g1", "wqkv", "wo", "g2", "wg", "wu", "wd", "gq", "gk")])
         self._chk(self.lib.pat_load_layer_from_full(self.ctx, layer, C.byref(lw)))
 
     def pat_load_final(self, w: dict):

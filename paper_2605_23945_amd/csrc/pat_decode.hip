@@ -36,7 +36,7 @@ struct WorkLayout {   // byte offsets inside the work arena
 
 struct WeightLayout {  // byte offsets inside the weights arena
     int64_t layer0, layer_stride;
-    int64_t g1, wqkv, wo, g2, wgu, wd;   // within a layer
+    int64_t g1, wqkv, wo, g2, wgu, wd, gq, gk;   // within a layer
     int64_t embed, gf, wlm, total;
 };
 
@@ -178,6 +178,8 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     o = 0;
     wt->g1 = take((int64_t)s.H * 2);
     wt->g2 = take((int64_t)s.H * 2);
+    wt->gq = take((int64_t)s.d * 2);
+    wt->gk = take((int64_t)s.d * 2);
     wt->wqkv = take(packed_w_bytes(s.qkv_rows, s.H));
     wt->wo = take(packed_w_bytes(s.H, s.hq * s.d));
     wt->wgu = take(packed_w_bytes(2 * s.F, s.H));
@@ -342,10 +344,15 @@ int pat_load_layer(pat_ctx *c, int32_t layer, const pat_layer_weights *w)
     if (!c) return PAT_EINVAL;
     if (!w || layer < 0 || layer >= c->sh.NL) return fail(c, PAT_EINVAL, "layer %d outside [0, %d)", layer, c->sh.NL);
     if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(c, PAT_EINVAL, "NULL weight pointer");
+    if (c->cfg.qk_norm && (!w->gq || !w->gk)) return fail(c, PAT_EINVAL, "qk_norm is set: gq and gk are required");
     const Shard &s = c->sh;
     char *L = at<char>(c->bufs.weights, c->wt.layer0 + c->wt.layer_stride * layer);
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    if (c->cfg.qk_norm) {
+        PAT_HIP(c, hipMemcpyAsync(L + c->wt.gq, w->gq, (size_t)s.d * 2, hipMemcpyDeviceToDevice, c->stream));
+        PAT_HIP(c, hipMemcpyAsync(L + c->wt.gk, w->gk, (size_t)s.d * 2, hipMemcpyDeviceToDevice, c->stream));
+    }
     PAT_HIP(c, launch_pack_weight_qkv((const uint16_t *)w->wqkv, s.qkv_rows, s.H, s.H, (s.hq + s.hkv) * s.d, s.d, (uint4 *)(L + c->wt.wqkv), c->stream));
     PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wo, nullptr, s.H, s.hq * s.d, s.hq * s.d, (uint4 *)(L + c->wt.wo), c->stream));
     PAT_HIP(c, launch_pack_weight((const uint16_t *)w->wg, (const uint16_t *)w->wu, s.F, s.H, s.H, (uint4 *)(L + c->wt.wgu), c->stream));
@@ -359,6 +366,7 @@ int pat_load_layer_from_full(pat_ctx *c, int32_t layer, const pat_layer_weights 
     if (!c) return PAT_EINVAL;
     if (!w || layer < 0 || layer >= c->sh.NL) return fail(c, PAT_EINVAL, "layer %d outside [0, %d)", layer, c->sh.NL);
     if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(c, PAT_EINVAL, "NULL weight pointer");
+    if (c->cfg.qk_norm && (!w->gq || !w->gk)) return fail(c, PAT_EINVAL, "qk_norm is set: gq and gk are required");
     const Shard &s = c->sh;
     const pat_cfg &m = c->cfg;
     const int tp = m.tp_degree, rank = m.tp_rank, d = s.d;
@@ -369,6 +377,10 @@ int pat_load_layer_from_full(pat_ctx *c, int32_t layer, const pat_layer_weights 
                    *wu = (const uint16_t *)w->wu, *wd = (const uint16_t *)w->wd;
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g1, w->g1, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
     PAT_HIP(c, hipMemcpyAsync(L + c->wt.g2, w->g2, (size_t)s.H * 2, hipMemcpyDeviceToDevice, c->stream));
+    if (c->cfg.qk_norm) {
+        PAT_HIP(c, hipMemcpyAsync(L + c->wt.gq, w->gq, (size_t)s.d * 2, hipMemcpyDeviceToDevice, c->stream));
+        PAT_HIP(c, hipMemcpyAsync(L + c->wt.gk, w->gk, (size_t)s.d * 2, hipMemcpyDeviceToDevice, c->stream));
+    }
     // q, k and v rows of this rank are three row ranges of the full matrix; each fills whole 16-row tiles
     // of the packed matrix (head_dim is a multiple of 16)
     uint4 *pq = (uint4 *)(L + c->wt.wqkv);
@@ -567,9 +579,19 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
             GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart);
-            g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len;
-            g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmQKV, st));
+            if (!c->cfg.qk_norm) {
+                g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len;
+                g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
+                TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmQKV, st));
+            } else {
+                // per-head q/k normalisation needs whole heads: plain projection, then one small kernel
+                // that normalises, rotates and appends
+                { TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st)); }
+                TimeScope t(c, 2);
+                PAT_HIP(c, launch_qknorm_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st.kv_len, c->st.page_table, s.max_pages,
+                                                     at<float>(W, w.rope), (const uint16_t *)(L + c->wt.gq),
+                                                     (const uint16_t *)(L + c->wt.gk), c->cfg.rms_eps, B, st));
+            }
         }
         aa.layer = l;
         { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }

@@ -95,6 +95,10 @@ hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, 
 hipError_t launch_compact(const StateArrays &st, int B, hipStream_t s);
 hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, uint16_t *k, uint16_t *v, int n_tokens,
                           int to_pool, hipStream_t s);
+// per-head q/k RMSNorm + rotary + KV append after a plain QKV projection (rows in the packed matrix's order)
+hipError_t launch_qknorm_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const int32_t *kv_len,
+                                     const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
+                                     const uint16_t *gk, float eps, int B, hipStream_t s);
 struct KvMoveArgs {
     KvLayout kv;
     const int32_t *slots, *tok_off;        // device: selected slots and the token offset of each in the buffer

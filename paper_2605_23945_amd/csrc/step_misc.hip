@@ -231,6 +231,49 @@ __global__ void kv_copy_kernel(KvLayout kv, int layer, const int32_t *pt_row, ui
     if (to_pool) { *pk = *fk; *pv = *fv; } else { *fk = *pk; *fv = *pv; }
 }
 
+// Model family with per-head q/k normalisation: after a plain QKV projection, one wave per
+// (batch row, head) RMS-normalises a q or k head over its d features (gains shared by the heads),
+// rotates it at the row's position and writes q back in natural order / k as bf16 into the row's
+// page; v heads are only rounded and stored.  The projection's q and k rows arrive in the packed
+// matrix's order: stored features (2j, 2j + 1) are natural (j, j + d/2), a rotary pair.
+__global__ __launch_bounds__(256) void qknorm_rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
+                                                                 const int32_t *kv_len, const int32_t *page_table,
+                                                                 int max_pages, const float *rope_cs, const uint16_t *gq,
+                                                                 const uint16_t *gk, float eps)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int head = blockIdx.x * 4 + wave, b = blockIdx.y;
+    const int D = kv.d, half = D >> 1, P = kv.P, hkv = kv.hkv;
+    if (head >= hq + 2 * hkv) return;
+    float *row = qkv + (int64_t)b * ldq + (int64_t)head * D;
+    const int pos = kv_len[b];
+    const bool on = lane < half;
+    const int j = on ? lane : 0;
+    const float2 v = *reinterpret_cast<const float2 *>(row + 2 * j);
+    if (head >= hq + hkv) {                           // a v head: natural order, two features per lane
+        if (on) {
+            const int page = page_table[(int64_t)b * max_pages + pos / P];
+            uint16_t *vd = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + ((int64_t)(head - hq - hkv) * P + (pos % P)) * D;
+            *reinterpret_cast<uint32_t *>(vd + 2 * j) = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+        }
+        return;
+    }
+    const float ss = wave_sum(on ? v.x * v.x + v.y * v.y : 0.f);      // every lane has loaded before any lane stores
+    const float inv = 1.0f / sqrtf(ss / (float)D + eps);
+    const uint16_t *g = head < hq ? gq : gk;
+    const float x0 = v.x * inv * bf16_to_f32(g[j]), x1 = v.y * inv * bf16_to_f32(g[j + half]);
+    const float2 cs = *reinterpret_cast<const float2 *>(rope_cs + ((int64_t)pos * half + j) * 2);
+    const float r0 = x0 * cs.x - x1 * cs.y, r1 = x0 * cs.y + x1 * cs.x;
+    if (!on) return;
+    if (head < hq) {
+        row[j] = r0; row[j + half] = r1;
+    } else {
+        const int page = page_table[(int64_t)b * max_pages + pos / P];
+        uint16_t *kd = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + ((int64_t)(head - hq) * P + (pos % P)) * D;
+        kd[j] = f32_to_bf16(r0); kd[j + half] = f32_to_bf16(r1);
+    }
+}
+
 // Valid K/V of selected slots <-> one contiguous buffer [layer][K|V][head][token][d], the tokens of
 // the selected slots back to back: the local half of the KV migration (gather what the unfinished
 // samples hold, or fill a head slice of freshly admitted slots from a gathered buffer).  Pure 16-byte
@@ -341,6 +384,16 @@ hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, 
     if (n_tokens <= 0) return hipSuccess;
     const int64_t n = (int64_t)n_tokens * (kv.hkv * kv.d / 8);
     kv_copy_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(kv, layer, pt_row, k, v, n_tokens, to_pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_qknorm_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const int32_t *kv_len,
+                                     const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
+                                     const uint16_t *gk, float eps, int B, hipStream_t s)
+{
+    if (B <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((hq + 2 * kv.hkv + 3) / 4), (unsigned)B);
+    qknorm_rope_append_kernel<<<grid, 256, 0, s>>>(qkv, ldq, hq, kv, layer, kv_len, page_table, max_pages, rope_cs, gq, gk, eps);
     return hipGetLastError();
 }
 

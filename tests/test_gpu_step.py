@@ -435,3 +435,37 @@ def test_weight_reslice_from_the_unsharded_layer_is_bitwise_the_shard(hq, hkv, t
         ref_logits, ref_next, _ = odec.step()
         check_logits(la, ref_logits)
         assert np.array_equal(na, ref_next)
+
+
+@pytest.mark.parametrize("hq,hkv,d,tp,rank", [(4, 4, 64, 1, 0), (8, 2, 128, 1, 0), (4, 4, 64, 2, 1)])
+def test_model_family_with_per_head_qk_norm(hq, hkv, d, tp, rank):
+    """The second model family of the paper's evaluation normalises every q and k head (RMSNorm over
+    head_dim, shared gains) before the rotary embedding: plain projection + one small kernel."""
+    m = pi.ModelShape(2, 256, hq, hkv, d, 512, 512, qk_norm=True)
+    _rollout_parity(pi.shard_of(m, tp, rank), 4, (20, 200), [3, 3, 2, 3])
+
+
+def test_per_head_qk_norm_at_live_batch_40_and_the_unsharded_loader():
+    m = pi.ModelShape(2, 256, 8, 4, 64, 1024, 1024, qk_norm=True)
+    shard = pi.shard_of(m, 2, 1)
+    _sampled_rows_parity(shard, 40, (30, 150), [0, 15, 16, 39], steps=2)
+    # the re-slice loader carries the gains too: same logits bit for bit
+    pat = _pat()
+    req = pi.rollout_requests(shard, 3, (20, 60), steps=3)
+    outs = []
+    for sliced in (False, True):
+        dec = pat.Decoder(pat.make_cfg(shard, 4, 128, 512, 16), DEV)
+        if sliced:
+            full = pi.shard_of(m, 1, 0)
+            for l in range(m.n_layers):
+                dec.pat_load_layer_from_full(l, pi.layer_weights(full, l, device=DEV))
+                torch.cuda.synchronize()
+            fw = pi.final_weights(shard, device=DEV); fw["embed"] = pi.embedding_table(shard, device=DEV)
+            dec.pat_load_final(fw)
+            torch.cuda.synchronize()
+        else:
+            pat.load_synthetic_weights(dec, shard, DEV)
+        pat.admit_synthetic(dec, shard, req, DEV)
+        outs.append(_gpu_step(dec, 3, shard.vocab)[0])
+        dec.close()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
