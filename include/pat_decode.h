@@ -162,6 +162,17 @@ int pat_kv_extract(pat_ctx *ctx, int32_t n, const int32_t *slots, int32_t layer0
 int pat_kv_inject(pat_ctx *ctx, int32_t n, const int32_t *slots, int32_t layer0, int32_t n_layers, int32_t pool_head0,
                   int32_t n_heads, const void *buf, int32_t buf_heads, int32_t buf_head0, int64_t t_sel);
 
+/* Recomputation, the other way to restore unfinished samples after a switch (Sec. 4.2: only the
+ * token sequences are transferred and the KV states are rebuilt by a prefill pass), and the way to
+ * build real prompt states at all.  For `n` live slots (host array, no repeats) admitted with their
+ * context lengths, `tokens` (host) holds, slot after slot in the given order, the kv_len[slot]
+ * token ids at positions 0 .. kv_len - 1; n_tokens is their total.  Fills K and V of those
+ * positions in every layer: each token runs through the layers as a row of a ragged batch (rows of
+ * several sequences share a pass), attending causally to the positions before it.  The slots'
+ * state (last token, lengths) is not changed: the next pat_decode_step continues from the
+ * admitted last token.  Waits for the GPU work of every pass (the staging is reused). */
+int pat_prefill(pat_ctx *ctx, int32_t n, const int32_t *slots, const int32_t *tokens, int64_t n_tokens);
+
 /* One decode step over the live batch: embedding, n_layers x (RMSNorm, QKV,
  * rotary + KV append, attention over the paged cache, O + residual, RMSNorm,
  * gate/up + SiLU*mul, down + residual), final RMSNorm, vocabulary-slice logits,

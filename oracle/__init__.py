@@ -278,3 +278,19 @@ def kv_extract(od: OracleDecoder, slots, layer0, n_layers, head0, n_heads):
                     out[l, 1, h, t] = od.vc[s][layer0 + l][tok, head0 + h]
                     t += 1
     return out
+
+
+def prefill(od: OracleDecoder, slot, tokens):
+    """Rebuild the K/V states of one live slot from its token ids (the recomputation way of restoring
+    a sample after a switch, Sec. 4.2: the token sequence is all that moves, a prefill pass builds
+    the states).  Causal attention written out as what it means: the token at position t is embedded
+    and taken through every layer with the cache holding positions 0 .. t-1, which appends its own
+    K/V at position t.  Overwrites positions 0 .. kv_len-1 of the slot's cache in every layer; the
+    slot's other state is untouched."""
+    NL, H, hq, hkv, d, F, eps, base = od.dims
+    L = int(od.kv_len[slot])
+    assert len(tokens) == L
+    for t in range(L):
+        x = od.o.embed(od.embed_row(int(tokens[t])))
+        for l in range(NL):
+            od.o.layer((H, hq, hkv, d, eps, base), F, od.layer_w(l), x, od.kc[slot][l], od.vc[slot][l], t)

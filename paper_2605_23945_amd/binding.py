@@ -79,7 +79,7 @@ class pat_switch_decision(C.Structure):
 
 
 EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_layer_from_full", "pat_load_final", "pat_decode_admit",
-           "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
+           "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
            "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
@@ -108,6 +108,7 @@ def load_library() -> C.CDLL:
     lib.pat_kv_read.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32]
     lib.pat_kv_extract.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int64, C.POINTER(C.c_int64)]
     lib.pat_kv_inject.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, C.c_int32, C.c_int64]
+    lib.pat_prefill.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int64]
     lib.pat_decode_step.argtypes = [vp, C.POINTER(pat_step_report), vp, vp]
     lib.pat_kv_compact.argtypes = [vp, i32p]
     lib.pat_get_state.argtypes = [vp, i32p] + [i32p] * 6
@@ -262,6 +263,11 @@ class Decoder:
         sl, slp = _i32(slots)
         self._chk(self.lib.pat_kv_inject(self.ctx, len(sl), slp, layer0, n_layers, pool_head0, n_heads,
                                          _ptr(buf), buf_heads, buf_head0, t))
+
+    def pat_prefill(self, slots, tokens):
+        """tokens: flat int32 array, the slots' token ids at positions 0 .. kv_len - 1, slot after slot."""
+        sl, slp = _i32(slots); tk, tkp = _i32(tokens)
+        self._chk(self.lib.pat_prefill(self.ctx, len(sl), slp, tkp, len(tk)))
 
     def pat_decode_step(self, report=True, next_tok=None, logits=None):
         rep = pat_step_report()

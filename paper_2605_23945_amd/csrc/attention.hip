@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         const int4 m1 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce + 1];
         const int b = m0.x, t0 = m0.y, cnt = m0.z;
         const bool rec_pages = C <= 4 * P;            // the record holds every page of the chunk
-        const int32_t *pt = a.page_table + (int64_t)b * a.max_pages;
+        const int32_t *pt = a.page_table + (int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages;
         const int pfirst = t0 / P;
         const int64_t head_off = (int64_t)h * P * D + seg * 8;
         // UR token rows per thread, requested together: page indices first (unconditional, clamped to

@@ -76,14 +76,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int qua
                 *reinterpret_cast<float2 *>(q + j0) = make_float2(r00, r10);
                 *reinterpret_cast<float2 *>(q + j0 + half) = make_float2(r01, r11);
             } else {
-                const int page = a.page_table[(int64_t)b * a.max_pages + pos / P];
+                const int page = a.page_table[(int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages + pos / P];
                 uint16_t *kd = a.kv.pool + a.kv.base(a.layer, 0) + page * a.kv.page_elems() +
                                ((int64_t)(head - a.hq) * P + (pos % P)) * D;
                 *reinterpret_cast<uint32_t *>(kd + j0) = (uint32_t)f32_to_bf16(r00) | ((uint32_t)f32_to_bf16(r10) << 16);
                 *reinterpret_cast<uint32_t *>(kd + j0 + half) = (uint32_t)f32_to_bf16(r01) | ((uint32_t)f32_to_bf16(r11) << 16);
             }
         } else {
-            const int page = a.page_table[(int64_t)b * a.max_pages + pos / P];
+            const int page = a.page_table[(int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages + pos / P];
             uint16_t *vd = a.kv.pool + a.kv.base(a.layer, 1) + page * a.kv.page_elems() +
                            ((int64_t)(head - a.hq - a.kv.hkv) * P + (pos % P)) * D + p0;
             *reinterpret_cast<uint2 *>(vd) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),

@@ -28,7 +28,7 @@ struct Shard {
 };
 
 struct WorkLayout {   // byte offsets inside the work arena
-    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, sel, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
+    int64_t x, a_hi, a_lo, b_hi, b_lo, qkv, sel, rows, gemm_part, part_acc, part_ml, logits, next_tok, best_val, rope, report;
     int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, chunk_meta, tmp;
     int64_t total;
     int64_t max_chunks;
@@ -143,7 +143,8 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     w->b_hi = take(packed_x_bytes(MB, kb));
     w->b_lo = take(packed_x_bytes(MB, kb));
     w->qkv = take((int64_t)MB * s.qkv_rows * 4);
-    w->sel = take((int64_t)2 * MB * 4);                 // selected slots and their token offsets (KV extract / inject)
+    w->sel = take((int64_t)2 * MB * 4);
+    w->rows = take((int64_t)3 * MB * 4);                // token, slot, position of the rows of a prefill pass                 // selected slots and their token offsets (KV extract / inject)
     {   // scratch for K-slice partial sums of the projections: the largest any (matrix, batch) needs
         const int mats[5][2] = {{s.qkv_rows / 16, s.H / 32}, {s.H / 16, s.hq * s.d / 32}, {2 * s.F / 16, s.H / 32},
                                 {s.H / 16, s.F / 32}, {s.Vs / 16, s.H / 32}};
@@ -247,7 +248,10 @@ hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
         h.xhi = g.xhi + t0 * g.KS * 64; h.xlo = g.xlo + t0 * g.KS * 64;
         if (g.y) h.y = g.y + (int64_t)b0 * g.ldy;
         if (g.yhi) { h.yhi = g.yhi + t0 * g.KS_out * 64; h.ylo = g.ylo + t0 * g.KS_out * 64; }
-        if (g.kv_len) { h.kv_len = g.kv_len + b0; h.page_table = g.page_table + (int64_t)b0 * g.max_pages; }
+        if (g.kv_len) {
+            h.kv_len = g.kv_len + b0;
+            if (g.row_slot) h.row_slot = g.row_slot + b0; else h.page_table = g.page_table + (int64_t)b0 * g.max_pages;
+        }
         hipError_t e = launch_gemm(h, mode, st);
         if (e != hipSuccess) return e;
     }
@@ -535,6 +539,64 @@ int pat_step_algo_bytes(pat_ctx *c, double *weight_bytes, double *kv_bytes)
     return PAT_OK;
 }
 
+// The transformer layers over B rows whose embeddings sit in x: row b is the token at position pos[b]
+// (= tokens cached before it) of slot row_slot[b] (NULL: slot b, the decode step).  The attention
+// chunk records of these rows must have been planned.  Leaves the rows' final hidden states in x.
+static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t *pos, const int32_t *row_slot)
+{
+    const Shard &s = c->sh;
+    void *W = c->bufs.work;
+    const WorkLayout &w = c->wl;
+    hipStream_t st = c->stream;
+    float *x = at<float>(W, w.x), *qkv = at<float>(W, w.qkv);
+    uint4 *a_hi = at<uint4>(W, w.a_hi), *a_lo = at<uint4>(W, w.a_lo), *b_hi = at<uint4>(W, w.b_hi), *b_lo = at<uint4>(W, w.b_lo);
+    char *Wb = at<char>(c->bufs.weights, 0);
+    float *gpart = at<float>(W, w.gemm_part);
+    AttnArgs aa{};
+    aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = pos; aa.row_slot = row_slot;
+    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_meta = c->st.chunk_meta; aa.chunk_tokens = C;
+    aa.part_acc = at<float>(W, w.part_acc); aa.part_ml = at<float>(W, w.part_ml); aa.ohi = b_hi; aa.olo = b_lo;
+    aa.n_items = (int)(n_chunks * s.hkv);
+
+    for (int l = 0; l < s.NL; ++l) {
+        char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
+            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart);
+            if (!c->cfg.qk_norm) {
+                g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = pos; g.row_slot = row_slot;
+                g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
+                TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmQKV, st));
+            } else {
+                // per-head q/k normalisation needs whole heads: plain projection, then one small kernel
+                // that normalises, rotates and appends
+                { TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st)); }
+                TimeScope t(c, 2);
+                PAT_HIP(c, launch_qknorm_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, pos, row_slot, c->st.page_table, s.max_pages,
+                                                     at<float>(W, w.rope), (const uint16_t *)(L + c->wt.gq),
+                                                     (const uint16_t *)(L + c->wt.gk), c->cfg.rms_eps, B, st));
+            }
+        }
+        aa.layer = l;
+        { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
+        {
+            GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart);
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
+        }
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        {
+            GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart);
+            g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
+        }
+        {
+            GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart);
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
+        }
+    }
+    return PAT_OK;
+}
+
 int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_dev, float *logits_dev)
 {
     if (!c) return PAT_EINVAL;
@@ -558,8 +620,8 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     void *W = c->bufs.work;
     const WorkLayout &w = c->wl;
     hipStream_t st = c->stream;
-    float *x = at<float>(W, w.x), *qkv = at<float>(W, w.qkv);
-    uint4 *a_hi = at<uint4>(W, w.a_hi), *a_lo = at<uint4>(W, w.a_lo), *b_hi = at<uint4>(W, w.b_hi), *b_lo = at<uint4>(W, w.b_lo);
+    float *x = at<float>(W, w.x);
+    uint4 *a_hi = at<uint4>(W, w.a_hi), *a_lo = at<uint4>(W, w.a_lo);
     float *logits = logits_dev ? logits_dev : at<float>(W, w.logits);
     int32_t *next_tok = next_tok_dev ? next_tok_dev : at<int32_t>(W, w.next_tok);
     char *Wb = at<char>(c->bufs.weights, 0);
@@ -568,48 +630,7 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     { TimeScope t(c, 2); PAT_HIP(c, launch_plan_step(c->st, B, C, st)); }
     { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
 
-    AttnArgs aa{};
-    aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = c->st.kv_len;
-    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_meta = c->st.chunk_meta; aa.chunk_tokens = C;
-    aa.part_acc = at<float>(W, w.part_acc); aa.part_ml = at<float>(W, w.part_ml); aa.ohi = b_hi; aa.olo = b_lo;
-    aa.n_items = (int)(n_chunks * s.hkv);
-
-    for (int l = 0; l < s.NL; ++l) {
-        char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
-        {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
-            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart);
-            if (!c->cfg.qk_norm) {
-                g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len;
-                g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
-                TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmQKV, st));
-            } else {
-                // per-head q/k normalisation needs whole heads: plain projection, then one small kernel
-                // that normalises, rotates and appends
-                { TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st)); }
-                TimeScope t(c, 2);
-                PAT_HIP(c, launch_qknorm_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st.kv_len, c->st.page_table, s.max_pages,
-                                                     at<float>(W, w.rope), (const uint16_t *)(L + c->wt.gq),
-                                                     (const uint16_t *)(L + c->wt.gk), c->cfg.rms_eps, B, st));
-            }
-        }
-        aa.layer = l;
-        { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
-        {
-            GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart);
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
-        }
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
-        {
-            GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart);
-            g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
-        }
-        {
-            GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart);
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
-        }
-    }
+    if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr)) return rc;
     { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
     {
         GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart);
@@ -641,6 +662,55 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
                             report_host->n_finished, (long long)report_host->sum_context, report_host->free_pages, n_fin,
                             (long long)sum_ctx, (long long)c->n_free);
         }
+    }
+    return PAT_OK;
+}
+
+int pat_prefill(pat_ctx *c, int32_t n, const int32_t *slots, const int32_t *tokens, int64_t n_tokens)
+{
+    if (!c) return PAT_EINVAL;
+    const Shard &s = c->sh;
+    if (n <= 0 || !slots || n_tokens < 0 || (n_tokens > 0 && !tokens)) return fail(c, PAT_EINVAL, "prefill: bad arguments");
+    for (int l = 0; l < s.NL; ++l) if (!c->layer_loaded[l]) return fail(c, PAT_ESTATE, "prefill: layer %d not loaded", l);
+    if (!c->final_loaded) return fail(c, PAT_ESTATE, "prefill: final weights (the embedding table) not loaded");
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (slots[i] < 0 || slots[i] >= c->live) return fail(c, PAT_EINVAL, "prefill: slot %d is not live", slots[i]);
+        for (int j = 0; j < i; ++j) if (slots[j] == slots[i]) return fail(c, PAT_EINVAL, "prefill: slot %d given twice", slots[i]);
+        if (c->fin[slots[i]]) return fail(c, PAT_ESTATE, "prefill: slot %d is finished", slots[i]);
+        total += c->kv_len[slots[i]];
+    }
+    if (total != n_tokens) return fail(c, PAT_EINVAL, "prefill: the slots hold %lld cached positions, %lld tokens given", (long long)total, (long long)n_tokens);
+    for (int64_t t = 0; t < n_tokens; ++t)
+        if (tokens[t] < 0 || tokens[t] >= s.V) return fail(c, PAT_EINVAL, "prefill: token id %d outside the vocabulary", tokens[t]);
+    if (n_tokens == 0) return PAT_OK;
+
+    const int MB = c->cfg.max_batch, R_max = MB, C = 256;
+    void *W = c->bufs.work;
+    int32_t *rows = at<int32_t>(W, c->wl.rows);
+    int32_t *p = c->pinned;
+    char *Wb = at<char>(c->bufs.weights, 0);
+    int si = 0, pos = 0;
+    int64_t t = 0;
+    while (t < n_tokens) {
+        // one pass: the next rows in (slot, position) order, as many as the work buffers and the
+        // attention workspace take; a row's keys are rows of this or an earlier pass
+        int R = 0;
+        int64_t chunks = 0;
+        while (R < R_max && t < n_tokens) {
+            while (pos >= c->kv_len[slots[si]]) { ++si; pos = 0; }
+            const int64_t need = (pos + 1 + C - 1) / C;
+            if (chunks + need > c->wl.max_chunks) break;
+            p[R] = tokens[t]; p[MB + R] = slots[si]; p[2 * MB + R] = pos;
+            chunks += need; ++R; ++t; ++pos;
+        }
+        if (R == 0) return fail(c, PAT_ENOMEM, "prefill: one row needs more attention chunks than the workspace holds");
+        for (int a = 0; a < 3; ++a)
+            PAT_HIP(c, hipMemcpyAsync(rows + a * MB, p + a * MB, (size_t)R * 4, hipMemcpyHostToDevice, c->stream));
+        PAT_HIP(c, launch_plan_rows(c->st, R, C, rows + MB, rows + 2 * MB, c->stream));
+        PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, rows, R, at<float>(W, c->wl.x), c->stream));
+        if (int rc = run_layers(c, R, C, chunks, rows + 2 * MB, rows + MB)) return rc;
+        PAT_HIP(c, hipStreamSynchronize(c->stream));     // the staging buffer is reused by the next pass
     }
     return PAT_OK;
 }

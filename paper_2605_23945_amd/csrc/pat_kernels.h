@@ -31,6 +31,7 @@ struct GemmArgs {
     KvLayout kv;
     int layer, hq, max_pages;
     const int32_t *kv_len, *page_table;
+    const int32_t *row_slot;   // slot (page-table row) of batch row b, or NULL: slot b
     const float *rope_cs;      // [pos][d/2][cos, sin]
     float *part;               // scratch for K-slice partials [Kb][B][n_tiles * 16], or NULL
     int Kb, Rg;                // set by launch_gemm from gemm_plan
@@ -60,6 +61,7 @@ struct AttnArgs {
     int ldq, hq, B;
     const int32_t *kv_len;     // tokens cached BEFORE this step (the new one sits at index kv_len)
     const int32_t *page_table; // [max_batch][max_pages]
+    const int32_t *row_slot;   // slot of batch row b, or NULL: slot b
     int max_pages;
     const int32_t *chunk_start;// [B + 1] exclusive prefix of per-slot chunk counts
     const int32_t *chunk_meta; // [n_chunks_total][8] written by plan_step (see StateArrays)
@@ -89,6 +91,8 @@ struct StateArrays {           // device int32 arrays of max_batch entries
 hipError_t launch_pool_init(const StateArrays &st, int n_pages, hipStream_t s);
 hipError_t launch_admit(const StateArrays &st, int live, int n, hipStream_t s);   // new slots' arrays already copied in
 hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipStream_t s);
+// chunk records for rows that are not slots (prefill): row i is position row_pos[i] of slot row_slot[i]
+hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, hipStream_t s);
 hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s);
 hipError_t launch_argmax(const float *logits, int B, int n, int base, int32_t *out_idx, float *out_val, hipStream_t s);
 hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, int eos, void *report_dev, hipStream_t s);
@@ -97,7 +101,7 @@ hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, 
                           int to_pool, hipStream_t s);
 // per-head q/k RMSNorm + rotary + KV append after a plain QKV projection (rows in the packed matrix's order)
 hipError_t launch_qknorm_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const int32_t *kv_len,
-                                     const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
+                                     const int32_t *row_slot, const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
                                      const uint16_t *gk, float eps, int B, hipStream_t s);
 struct KvMoveArgs {
     KvLayout kv;

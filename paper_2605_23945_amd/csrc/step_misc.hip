@@ -100,6 +100,35 @@ __global__ __launch_bounds__(kBlk) void plan_step_kernel(StateArrays st, int B, 
     }
 }
 
+// Chunk prefix and chunk records for R rows that are positions of slots (prefill: row i is the token
+// at position row_pos[i] of slot row_slot[i], attending to positions 0 .. row_pos[i]).  No pages are
+// taken: the slots own the pages of their whole context since admission.
+__global__ __launch_bounds__(kBlk) void plan_rows_kernel(StateArrays st, int R, int C, const int32_t *row_slot,
+                                                         const int32_t *row_pos)
+{
+    __shared__ int s_start[kBlk + 1];
+    const int i = threadIdx.x;
+    const int chunks = (i < R) ? (row_pos[i] + 1 + C - 1) / C : 0;
+    int tot_c;
+    const int off_c = block_exclusive_scan(chunks, tot_c);
+    if (i < R) { st.chunk_start[i] = off_c; s_start[i] = off_c; }
+    if (i == 0) { st.chunk_start[R] = tot_c; s_start[R] = tot_c; }
+    __syncthreads();
+    const int n_rec = min(tot_c, st.max_chunks);
+    for (int ce = i; ce < n_rec; ce += kBlk) {
+        int lo = 0, hi = R;
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_start[mid] <= ce) lo = mid; else hi = mid; }
+        const int b = lo, t0 = (ce - s_start[b]) * C;
+        const int cnt = min(row_pos[b] + 1 - t0, C);
+        const int32_t *pt = st.page_table + (int64_t)row_slot[b] * st.max_pages;
+        const int p0 = t0 / st.P, plast = (t0 + cnt - 1) / st.P;
+        int4 m0 = make_int4(b, t0, cnt, 0), m1;
+        m1.x = pt[p0]; m1.y = pt[min(p0 + 1, plast)]; m1.z = pt[min(p0 + 2, plast)]; m1.w = pt[min(p0 + 3, plast)];
+        reinterpret_cast<int4 *>(st.chunk_meta)[2 * (int64_t)ce] = m0;
+        reinterpret_cast<int4 *>(st.chunk_meta)[2 * (int64_t)ce + 1] = m1;
+    }
+}
+
 __global__ void embed_kernel(const uint16_t *table, int H, const int32_t *tok, float *x)
 {
     const int b = blockIdx.x;
@@ -237,8 +266,8 @@ __global__ void kv_copy_kernel(KvLayout kv, int layer, const int32_t *pt_row, ui
 // page; v heads are only rounded and stored.  The projection's q and k rows arrive in the packed
 // matrix's order: stored features (2j, 2j + 1) are natural (j, j + d/2), a rotary pair.
 __global__ __launch_bounds__(256) void qknorm_rope_append_kernel(float *qkv, int ldq, int hq, KvLayout kv, int layer,
-                                                                 const int32_t *kv_len, const int32_t *page_table,
-                                                                 int max_pages, const float *rope_cs, const uint16_t *gq,
+                                                                 const int32_t *kv_len, const int32_t *row_slot,
+                                                                 const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
                                                                  const uint16_t *gk, float eps)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -252,7 +281,7 @@ __global__ __launch_bounds__(256) void qknorm_rope_append_kernel(float *qkv, int
     const float2 v = *reinterpret_cast<const float2 *>(row + 2 * j);
     if (head >= hq + hkv) {                           // a v head: natural order, two features per lane
         if (on) {
-            const int page = page_table[(int64_t)b * max_pages + pos / P];
+            const int page = page_table[(int64_t)(row_slot ? row_slot[b] : b) * max_pages + pos / P];
             uint16_t *vd = kv.pool + kv.base(layer, 1) + page * kv.page_elems() + ((int64_t)(head - hq - hkv) * P + (pos % P)) * D;
             *reinterpret_cast<uint32_t *>(vd + 2 * j) = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
         }
@@ -268,7 +297,7 @@ __global__ __launch_bounds__(256) void qknorm_rope_append_kernel(float *qkv, int
     if (head < hq) {
         row[j] = r0; row[j + half] = r1;
     } else {
-        const int page = page_table[(int64_t)b * max_pages + pos / P];
+        const int page = page_table[(int64_t)(row_slot ? row_slot[b] : b) * max_pages + pos / P];
         uint16_t *kd = kv.pool + kv.base(layer, 0) + page * kv.page_elems() + ((int64_t)(head - hq) * P + (pos % P)) * D;
         kd[j] = f32_to_bf16(r0); kd[j + half] = f32_to_bf16(r1);
     }
@@ -349,6 +378,13 @@ hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipS
     return hipGetLastError();
 }
 
+hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, hipStream_t s)
+{
+    if (R <= 0 || R > kBlk) return hipErrorInvalidValue;
+    plan_rows_kernel<<<1, kBlk, 0, s>>>(st, R, chunk_tokens, row_slot, row_pos);
+    return hipGetLastError();
+}
+
 hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s)
 {
     embed_kernel<<<B, 256, 0, s>>>(table, H, tok, x);
@@ -388,12 +424,12 @@ hipError_t launch_kv_copy(const KvLayout &kv, int layer, const int32_t *pt_row, 
 }
 
 hipError_t launch_qknorm_rope_append(float *qkv, int ldq, int hq, const KvLayout &kv, int layer, const int32_t *kv_len,
-                                     const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
+                                     const int32_t *row_slot, const int32_t *page_table, int max_pages, const float *rope_cs, const uint16_t *gq,
                                      const uint16_t *gk, float eps, int B, hipStream_t s)
 {
     if (B <= 0) return hipSuccess;
     const dim3 grid((unsigned)((hq + 2 * kv.hkv + 3) / 4), (unsigned)B);
-    qknorm_rope_append_kernel<<<grid, 256, 0, s>>>(qkv, ldq, hq, kv, layer, kv_len, page_table, max_pages, rope_cs, gq, gk, eps);
+    qknorm_rope_append_kernel<<<grid, 256, 0, s>>>(qkv, ldq, hq, kv, layer, kv_len, row_slot, page_table, max_pages, rope_cs, gq, gk, eps);
     return hipGetLastError();
 }
 

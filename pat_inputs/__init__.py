@@ -33,5 +33,6 @@ from .workload import (  # noqa: F401
     layer_weights,
     final_weights,
     kv_prefix,
+    prompt_tokens,
     rollout_requests,
 )

@@ -181,6 +181,11 @@ def kv_prefix(s: ShardShape, seq_id: int, layer: int, length: int, device="cpu",
     return kk, vv
 
 
+def prompt_tokens(s: ShardShape, seq_id: int, n: int, seed=SEED_TOKENS):
+    """The n token ids of one request's prompt (uniform over the vocabulary), for the prefill path."""
+    return uniform_int(stream_key(seed, 1000 + int(seq_id)), int(n), 0, s.model.vocab - 1).astype(np.int32)
+
+
 def rollout_requests(s: ShardShape, n: int, prompt_len, resp=None, steps=None, seed=SEED_TOKENS):
     """n requests: (seq_id, first input token, prompt KV length, response length).
 

@@ -77,7 +77,7 @@ def check_logits(got: np.ndarray, ref: np.ndarray, tol=TOL, design_tol=DESIGN_TO
     return worst
 
 
-def bf16_close(a_bits: np.ndarray, b_bits: np.ndarray):
+def bf16_close(a_bits: np.ndarray, b_bits: np.ndarray, abs_tol=KV_ABS_TOL):
     """(fraction bit-identical, all within one bf16 step).
 
     The fp32 k, v that get rounded already differ from the oracle's by the path's accumulated
@@ -86,5 +86,5 @@ def bf16_close(a_bits: np.ndarray, b_bits: np.ndarray):
     plus KV_ABS_TOL of the tensor's rms."""
     same = a_bits == b_bits
     a, b = widen(a_bits), widen(b_bits)
-    step = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + KV_ABS_TOL * float(np.sqrt(np.mean(b * b)))
+    step = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + abs_tol * float(np.sqrt(np.mean(b * b)))
     return float(same.mean()), bool(np.all(np.abs(a - b) <= step))

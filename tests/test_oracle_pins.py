@@ -433,3 +433,63 @@ def test_decoder_compaction_preserves_survivors(orc):
     la, na, _ = dec.step()
     lb, nb_, _ = solo.step()
     assert np.array_equal(la, lb) and np.array_equal(na, nb_)
+
+
+# ---- prefill (an off-by-one in the causal window, a rotation at the wrong position) ----------
+
+def _torch_prefill(shard, lw, emb, tokens):
+    """All positions of one sequence at once, as matrices with the library's causal mask: K/V bits
+    [layer][T, hkv, d] of the whole sequence."""
+    m = shard.model
+    H, hq, hkv, d = m.hidden, shard.hq, shard.hkv, m.head_dim
+    T = len(tokens)
+    X = torch.stack([_w64(emb[int(t)]) for t in tokens])                       # [T, H]
+    pos = torch.arange(T, dtype=torch.float64)
+    inv = m.rope_base ** (-2.0 * torch.arange(d // 2, dtype=torch.float64) / d)
+    rot = torch.polar(torch.ones(T, d // 2, dtype=torch.float64), pos[:, None] * inv[None])   # [T, d/2]
+
+    def rope(a):                                                               # [T, heads, d]
+        z = torch.complex(a[..., : d // 2], a[..., d // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], -1)
+
+    ks, vs = [], []
+    for w in lw:
+        h = F.rms_norm(X, (H,), _w64(w["g1"]), eps=m.rms_eps)
+        qkv = h @ _w64(w["wqkv"]).T
+        q = rope(qkv[:, : hq * d].reshape(T, hq, d))
+        k = rope(qkv[:, hq * d:(hq + hkv) * d].reshape(T, hkv, d))
+        v = qkv[:, (hq + hkv) * d:].reshape(T, hkv, d)
+        kb = bits(k.to(torch.float32).to(torch.bfloat16)); vb = bits(v.to(torch.float32).to(torch.bfloat16))
+        ks.append(kb); vs.append(vb)
+        o = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], _w64(kb).permute(1, 0, 2)[None],
+                                           _w64(vb).permute(1, 0, 2)[None], is_causal=True, enable_gqa=True)
+        X = X + o[0].permute(1, 0, 2).reshape(T, hq * d) @ _w64(w["wo"]).T
+        h = F.rms_norm(X, (H,), _w64(w["g2"]), eps=m.rms_eps)
+        X = X + (F.silu(h @ _w64(w["wg"]).T) * (h @ _w64(w["wu"]).T)) @ _w64(w["wd"]).T
+    return ks, vs
+
+
+def test_prefill_vs_whole_sequence_causal_attention_of_the_library(orc):
+    """The oracle's token-by-token prefill against the matrix form with a causal mask.  Layer 2's
+    K/V depend on layer 1's attention output at every position, so a window that is one position
+    short or long, or a rotation by the wrong position, changes them."""
+    from oracle import prefill
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    m = shard.model
+    dec, req, emb, fw = _tiny_decoder(orc, shard, n_seq=2)
+    lw = [dec.layer_w(l) for l in range(m.n_layers)]
+    for slot in range(2):
+        T = int(dec.kv_len[slot])
+        toks = RNG.integers(0, shard.vocab, T)
+        before = [dec.kc[slot][l].copy() for l in range(m.n_layers)]
+        prefill(dec, slot, toks)
+        ks, vs = _torch_prefill(shard, lw, emb, toks)
+        for l in range(m.n_layers):
+            assert not np.array_equal(dec.kc[slot][l][:T], before[l][:T])       # the synthetic prefix was replaced
+            assert np.array_equal(dec.kc[slot][l][:T], ks[l]), f"K layer {l}"
+            assert np.array_equal(dec.vc[slot][l][:T], vs[l]), f"V layer {l}"
+            assert np.array_equal(dec.kc[slot][l][T:], before[l][T:])           # nothing written past the sequence
+    # the slots' step state is untouched and the next step runs from the rebuilt cache
+    assert np.array_equal(dec.kv_len, req["kv_len"]) and np.all(dec.gen == 0)
+    dec.step()
+    assert np.array_equal(dec.kv_len, req["kv_len"] + 1)
