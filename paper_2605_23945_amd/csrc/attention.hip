@@ -1,14 +1,15 @@
 // Split-KV decode attention over the ragged, paged bf16 cache.
 //
-// Work item = (sequence, chunk of up to `chunk_tokens` cached positions, KV head).
-// The flat item list covers the whole live batch, so one long sequence on a
-// shard with a single KV head still spreads over the chip, and neighbouring
-// items read neighbouring heads of the same pages.  A workgroup streams the
-// chunk's K rows (16-byte vectors, one token row = D/8 lanes), keeps the scores
-// of the G query heads that share this KV head in LDS, takes the chunk maximum,
-// then streams V once, accumulating exp(s - m) * V in registers.  It emits the
-// partial (m, l, acc); a second kernel merges a sequence's partials with the
-// online-softmax identity in a fixed order, so the result is run-to-run identical.
+// Work item = (sequence, chunk of up to `chunk_tokens` cached positions, KV head), one workgroup
+// each.  The flat item list covers the whole live batch, so one long sequence on a shard with a
+// single KV head still spreads over the chip, and neighbouring items read neighbouring heads of
+// the same pages.  Two kernels produce an item's partial (m, l, acc):
+//   * G < 4 query heads per KV head (attn_stream_kernel): one pass, K and V rows of a round of
+//     tokens in flight together and one round ahead, an online-softmax state per wave;
+//   * G >= 4 (attn_partial_kernel): scores as matrix products into LDS, chunk maximum, then one
+//     pass over V.
+// A second kernel merges a sequence's partials with the online-softmax identity in a fixed
+// order, so the result is run-to-run identical.
 #include "pat_dev.h"
 #include "pat_kernels.h"
 
@@ -22,6 +23,7 @@ constexpr int kMaxChunk = 256;
 template <int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
 {
+    static_assert(G >= 4, "scores on the matrix cores: for several query heads per KV head");
     constexpr int LPT = D / 8;                  // lanes per token row
     constexpr int TPR = kAttnThreads / LPT;     // token rows per round of the workgroup
     constexpr int UR = 4;                       // rounds in flight
@@ -70,19 +72,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
             __builtin_amdgcn_sched_barrier(0);
         };
 
-        constexpr bool kMatrixQK = G >= 4;      // scores on the matrix cores when several query heads share the KV head
-        float q[kMatrixQK ? 1 : G][8];
-        if (!kMatrixQK) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + g) * D + seg * 8;
-                const float4 q0 = *reinterpret_cast<const float4 *>(qp);
-                const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
-                q[g][0] = q0.x; q[g][1] = q0.y; q[g][2] = q0.z; q[g][3] = q0.w;
-                q[g][4] = q1.x; q[g][5] = q1.y; q[g][6] = q1.z; q[g][7] = q1.w;
-            }
-        }
-
         // The first batch of V rows is requested together with the K rows: a short chunk then
         // pays one memory latency instead of two.
         uint4 vfirst[UR];
@@ -90,7 +79,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
         load_rows(vbase, 0, vfirst, okv);
 
         // ---- scores of the chunk ----
-        if (kMatrixQK) {
+        {
             // S[query head, token] = Q K^T as 16 x 16 x 32 matrix products: the A operand holds the G
             // query heads of this KV head as rows (rows G..15 are zero), split into two bf16 terms so
             // that the products keep fp32-class accuracy; the B operand is 16 token rows of K, each
@@ -151,27 +140,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
                     }
                 }
             }
-        } else {
-        for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
-            uint4 kv[UR];
-            bool ok[UR];
-            load_rows(kbase, r0, kv, ok);
-#pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const float k0 = bf16lo(kv[u].x), k1 = bf16hi(kv[u].x), k2 = bf16lo(kv[u].y), k3 = bf16hi(kv[u].y);
-                const float k4 = bf16lo(kv[u].z), k5 = bf16hi(kv[u].z), k6 = bf16lo(kv[u].w), k7 = bf16hi(kv[u].w);
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float s = q[g][0] * k0;
-                    s = fmaf(q[g][1], k1, s); s = fmaf(q[g][2], k2, s); s = fmaf(q[g][3], k3, s);
-                    s = fmaf(q[g][4], k4, s); s = fmaf(q[g][5], k5, s); s = fmaf(q[g][6], k6, s);
-                    s = fmaf(q[g][7], k7, s);
-#pragma unroll
-                    for (int o = LPT / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-                    if (seg == 0 && ok[u]) sc[g * kMaxChunk + r0 + u * TPR + ts] = s * scale;
-                }
-            }
-        }
         }
         __syncthreads();
 
@@ -249,6 +217,192 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
     }
 }
 
+// The same work item for G < 4 (no matrix products), as one pass: K and V rows of a round of
+// tokens are requested together, one round ahead of the arithmetic, and every wave keeps an
+// online-softmax state (running maximum, denominator, weighted V sum) over its own token rows,
+// so nothing but the final combination of the four waves' states goes through LDS and no
+// barrier separates the K stream from the V stream.
+template <int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnArgs a)
+{
+    constexpr int LPT = D / 8;                  // lanes per token row
+    constexpr int TPR = kAttnThreads / LPT;     // token rows per sub-round of the workgroup
+    constexpr int UR = 4;                       // sub-rounds per round
+    constexpr int RT = TPR * UR;                // tokens per round
+    __shared__ float red[4 * G * D];
+    __shared__ float wml[4 * G * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ts = tid / LPT, seg = tid % LPT;
+    const int hkv = a.kv.hkv, P = a.kv.P, C = a.chunk_tokens;
+    const float scale = rsqrtf((float)D);
+    const uint16_t *kbase = a.kv.pool + a.kv.base(a.layer, 0);
+    const uint16_t *vbase = a.kv.pool + a.kv.base(a.layer, 1);
+    const int64_t page_elems = a.kv.page_elems();
+
+    for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+        const int ce = item / hkv, h = item - ce * hkv;
+        const int4 m0 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce];
+        const int4 m1 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce + 1];
+        const int b = m0.x, t0 = m0.y, cnt = m0.z;
+        const bool rec_pages = C <= 4 * P;
+        const int32_t *pt = a.page_table + (int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages;
+        const int pfirst = t0 / P;
+        const int64_t head_off = (int64_t)h * P * D + seg * 8;
+
+        // K and V rows of one round: addresses first (unconditional, clamped to the chunk's last
+        // token), then all 2 UR loads back to back
+        auto fetch = [&](int r0, u32x4_t (&kr)[UR], u32x4_t (&vr)[UR]) {
+            int64_t off[UR];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const int tc = t0 + min(r0 + u * TPR + ts, cnt - 1);
+                int page;
+                if (rec_pages) {
+                    const int j = tc / P - pfirst;
+                    page = j == 0 ? m1.x : j == 1 ? m1.y : j == 2 ? m1.z : m1.w;
+                } else {
+                    page = pt[tc / P];
+                }
+                off[u] = page * page_elems + head_off + (int64_t)(tc % P) * D;
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u) kr[u] = *reinterpret_cast<const u32x4_t *>(kbase + off[u]);
+#pragma unroll
+            for (int u = 0; u < UR; ++u) vr[u] = *reinterpret_cast<const u32x4_t *>(vbase + off[u]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        float q[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + g) * D + seg * 8;
+            const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+            const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+            q[g][0] = q0.x * scale; q[g][1] = q0.y * scale; q[g][2] = q0.z * scale; q[g][3] = q0.w * scale;
+            q[g][4] = q1.x * scale; q[g][5] = q1.y * scale; q[g][6] = q1.z * scale; q[g][7] = q1.w * scale;
+        }
+        float acc[G][8], den[G], M[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            den[g] = 0.f; M[g] = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
+        }
+
+        auto consume = [&](int r0, const u32x4_t (&kr)[UR], const u32x4_t (&vr)[UR]) {
+            float sv[UR][G];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const float k0 = bf16lo(kr[u].x), k1 = bf16hi(kr[u].x), k2 = bf16lo(kr[u].y), k3 = bf16hi(kr[u].y);
+                const float k4 = bf16lo(kr[u].z), k5 = bf16hi(kr[u].z), k6 = bf16lo(kr[u].w), k7 = bf16hi(kr[u].w);
+                const bool ok = r0 + u * TPR + ts < cnt;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float s = q[g][0] * k0;
+                    s = fmaf(q[g][1], k1, s); s = fmaf(q[g][2], k2, s); s = fmaf(q[g][3], k3, s);
+                    s = fmaf(q[g][4], k4, s); s = fmaf(q[g][5], k5, s); s = fmaf(q[g][6], k6, s);
+                    s = fmaf(q[g][7], k7, s);
+#pragma unroll
+                    for (int o = LPT / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+                    sv[u][g] = ok ? s : -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float mr = sv[0][g];
+#pragma unroll
+                for (int u = 1; u < UR; ++u) mr = fmaxf(mr, sv[u][g]);
+#pragma unroll
+                for (int o = 32; o >= LPT; o >>= 1) mr = fmaxf(mr, __shfl_xor(mr, o, 64));
+                const float Mn = fmaxf(M[g], mr);                    // the same in every lane of the wave
+                if (Mn == -INFINITY) continue;                       // this wave has seen no token yet
+                const float corr = expf(M[g] - Mn);                  // 0 on the wave's first tokens
+                M[g] = Mn;
+                den[g] *= corr;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[g][j] *= corr;
+#pragma unroll
+                for (int u = 0; u < UR; ++u) sv[u][g] = expf(sv[u][g] - Mn);     // exp(-inf) = 0 past the chunk
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const float v0 = bf16lo(vr[u].x), v1 = bf16hi(vr[u].x), v2 = bf16lo(vr[u].y), v3 = bf16hi(vr[u].y);
+                const float v4 = bf16lo(vr[u].z), v5 = bf16hi(vr[u].z), v6 = bf16lo(vr[u].w), v7 = bf16hi(vr[u].w);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    if (M[g] == -INFINITY) continue;                 // sv still holds -inf scores, not weights
+                    const float p = sv[u][g];
+                    den[g] += p;
+                    acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
+                    acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
+                    acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
+                    acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
+                }
+            }
+        };
+
+        u32x4_t kA[UR], vA[UR], kB[UR], vB[UR];
+        fetch(0, kA, vA);
+        for (int r0 = 0; r0 < cnt; r0 += 2 * RT) {
+            const bool second = r0 + RT < cnt;
+            if (second) fetch(r0 + RT, kB, vB);
+            consume(r0, kA, vA);
+            if (second) {
+                if (r0 + 2 * RT < cnt) fetch(r0 + 2 * RT, kA, vA);
+                consume(r0 + RT, kB, vB);
+            }
+        }
+
+        // the wave's rows: lanes at distance LPT, 2 LPT, ... hold the same feature segment
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int o = 32; o >= LPT; o >>= 1) den[g] += __shfl_xor(den[g], o, 64);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float v = acc[g][j];
+#pragma unroll
+                for (int o = 32; o >= LPT; o >>= 1) v += __shfl_xor(v, o, 64);
+                acc[g][j] = v;
+            }
+        }
+        if (lane < LPT) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) red[(wave * G + g) * D + lane * 8 + j] = acc[g][j];
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) { wml[(wave * G + g) * 2] = M[g]; wml[(wave * G + g) * 2 + 1] = den[g]; }
+        }
+        __syncthreads();
+        // the four waves' states in wave order; wave 0 always holds the chunk's first token
+        for (int e = tid; e < G * D + G; e += kAttnThreads) {
+            const int g = e < G * D ? e / D : e - G * D;
+            float mw[4], Mc = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mw[w] = wml[(w * G + g) * 2]; Mc = fmaxf(Mc, mw[w]); }
+            float sw[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sw[w] = mw[w] == -INFINITY ? 0.f : expf(mw[w] - Mc);
+            if (e < G * D) {
+                const int dd = e - g * D;
+                a.part_acc[((int64_t)ce * a.hq + h * G + g) * D + dd] =
+                    (red[(0 * G + g) * D + dd] * sw[0] + red[(1 * G + g) * D + dd] * sw[1]) +
+                    (red[(2 * G + g) * D + dd] * sw[2] + red[(3 * G + g) * D + dd] * sw[3]);
+            } else {
+                float *ml = a.part_ml + ((int64_t)ce * a.hq + h * G + g) * 2;
+                ml[0] = Mc;
+                ml[1] = (wml[(0 * G + g) * 2 + 1] * sw[0] + wml[(1 * G + g) * 2 + 1] * sw[1]) +
+                        (wml[(2 * G + g) * 2 + 1] * sw[2] + wml[(3 * G + g) * 2 + 1] * sw[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // One wave per (sequence, query head): lanes = D/8 feature segments x 64/(D/8) chunk lanes.
 // A chunk lane folds the chunks c = lane, lane + CL, ... in increasing order, then the chunk
 // lanes are combined pairwise in a fixed tree (online-softmax identity), so the result is
@@ -321,8 +475,8 @@ hipError_t launch_partial_d(const AttnArgs &a, int grid, hipStream_t s)
 {
     const int G = a.hq / a.kv.hkv;
     switch (G) {
-    case 1: attn_partial_kernel<D, 1><<<grid, kAttnThreads, 0, s>>>(a); break;
-    case 2: attn_partial_kernel<D, 2><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 1: attn_stream_kernel<D, 1><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 2: attn_stream_kernel<D, 2><<<grid, kAttnThreads, 0, s>>>(a); break;
     case 4: attn_partial_kernel<D, 4><<<grid, kAttnThreads, 0, s>>>(a); break;
     case 8: attn_partial_kernel<D, 8><<<grid, kAttnThreads, 0, s>>>(a); break;
     default: return hipErrorInvalidValue;
@@ -336,7 +490,7 @@ hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s)
 {
     if (a.n_items <= 0) return hipSuccess;
     if (a.chunk_tokens > kMaxChunk || a.chunk_tokens <= 0) return hipErrorInvalidValue;
-    const int grid = a.n_items < 4096 ? a.n_items : 4096;
+    const int grid = a.n_items;          // one workgroup per item: measured faster than any capped grid with a loop
     if (a.kv.d == 128) return launch_partial_d<128>(a, grid, s);
     if (a.kv.d == 64) return launch_partial_d<64>(a, grid, s);
     return hipErrorInvalidValue;

@@ -260,14 +260,17 @@ hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
 
 int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
 {
-    // largest chunk that still gives the chip about 8 work items per compute unit
+    // largest chunk that still gives the chip a few work items per compute unit (measured: the
+    // one-pass kernel of G < 4 wants about 4 per unit, the matrix-score kernel of G >= 4, whose
+    // items are G times as much arithmetic per byte, about 2)
+    const int thr = c->sh.hq / c->sh.hkv >= 4 ? 512 : 1024;
     int best = kMinChunk;
     int64_t best_n = 0;
     for (int C : {256, 128, 64}) {
         int64_t n = 0;
         for (int i = 0; i < c->live; ++i) n += (c->kv_len[i] + 1 + C - 1) / C;
         best = C; best_n = n;
-        if (n * c->sh.hkv >= 2048) break;
+        if (n * c->sh.hkv >= thr) break;
     }
     *n_chunks = best_n;
     return best;
