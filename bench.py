@@ -173,7 +173,7 @@ def main():
     if len(ps) and n_gemm:
         gemm_b, attn_b = float(wbytes[ps].sum()), float(kvbytes[ps].sum())
         cand = {"gemm_xs_kernel / gemm_xb_kernel (+ gemm_reduce_kernel): weight-streaming projections": (gemm_b, t_gemm, n_gemm),
-                "attn_partial_kernel + attn_merge_kernel (paged split-KV attention)": (attn_b, t_attn, n_attn)}
+                "attn_stream_kernel + attn_merge_kernel (paged split-KV attention)": (attn_b, t_attn, n_attn)}
         name = max(cand, key=lambda k: cand[k][1])
         def obj(k):
             b, t, cnt = cand[k]
