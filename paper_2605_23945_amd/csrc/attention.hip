@@ -6,8 +6,8 @@
 // the same pages.  Two kernels produce an item's partial (m, l, acc):
 //   * G < 4 query heads per KV head (attn_stream_kernel): one pass, K and V rows of a round of
 //     tokens in flight together and one round ahead, an online-softmax state per wave;
-//   * G >= 4 (attn_partial_kernel): scores as matrix products into LDS, chunk maximum, then one
-//     pass over V.
+//   * G >= 4 (attn_gqa_kernel): the same one-pass structure with the scores of a wave's 16 tokens
+//     against all G heads as matrix products.
 // A second kernel merges a sequence's partials with the online-softmax identity in a fixed
 // order, so the result is run-to-run identical.
 #include "pat_dev.h"
@@ -18,206 +18,9 @@ namespace pat {
 namespace {
 
 constexpr int kAttnThreads = 256;
-constexpr int kMaxChunk = 256;
+constexpr int kMaxChunk = 1024;
 
-template <int D, int G>
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(AttnArgs a)
-{
-    static_assert(G >= 4, "scores on the matrix cores: for several query heads per KV head");
-    constexpr int LPT = D / 8;                  // lanes per token row
-    constexpr int TPR = kAttnThreads / LPT;     // token rows per round of the workgroup
-    constexpr int UR = 4;                       // rounds in flight
-    __shared__ float sc[G * kMaxChunk];
-    __shared__ float red[4 * G * D];
-    __shared__ float ml[2 * G];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ts = tid / LPT, seg = tid % LPT;
-    const int hkv = a.kv.hkv, P = a.kv.P, C = a.chunk_tokens;
-    const float scale = rsqrtf((float)D);
-    const uint16_t *kbase = a.kv.pool + a.kv.base(a.layer, 0);
-    const uint16_t *vbase = a.kv.pool + a.kv.base(a.layer, 1);
-    const int64_t page_elems = a.kv.page_elems();
-
-    for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
-        const int ce = item / hkv, h = item - ce * hkv;
-        // one record per chunk (written by plan_step): slot, first token, token count, page ids
-        const int4 m0 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce];
-        const int4 m1 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce + 1];
-        const int b = m0.x, t0 = m0.y, cnt = m0.z;
-        const bool rec_pages = C <= 4 * P;            // the record holds every page of the chunk
-        const int32_t *pt = a.page_table + (int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages;
-        const int pfirst = t0 / P;
-        const int64_t head_off = (int64_t)h * P * D + seg * 8;
-        // UR token rows per thread, requested together: page indices first (unconditional, clamped to
-        // the chunk's last token), then the rows.  Conditional loads would serialise into
-        // load / wait pairs and leave one row in flight per thread.
-        auto load_rows = [&](const uint16_t *base, int r0, uint4 (&rows)[UR], bool (&okk)[UR]) {
-            int page[UR], tc[UR];
-#pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const int tl = r0 + u * TPR + ts;
-                okk[u] = tl < cnt;
-                tc[u] = t0 + min(tl, cnt - 1);
-                if (rec_pages) {
-                    const int j = tc[u] / P - pfirst;
-                    page[u] = j == 0 ? m1.x : j == 1 ? m1.y : j == 2 ? m1.z : m1.w;
-                } else {
-                    page[u] = pt[tc[u] / P];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < UR; ++u)
-                rows[u] = *reinterpret_cast<const uint4 *>(base + page[u] * page_elems + head_off + (int64_t)(tc[u] % P) * D);
-            __builtin_amdgcn_sched_barrier(0);
-        };
-
-        // The first batch of V rows is requested together with the K rows: a short chunk then
-        // pays one memory latency instead of two.
-        uint4 vfirst[UR];
-        bool okv[UR];
-        load_rows(vbase, 0, vfirst, okv);
-
-        // ---- scores of the chunk ----
-        {
-            // S[query head, token] = Q K^T as 16 x 16 x 32 matrix products: the A operand holds the G
-            // query heads of this KV head as rows (rows G..15 are zero), split into two bf16 terms so
-            // that the products keep fp32-class accuracy; the B operand is 16 token rows of K, each
-            // lane taking 8 consecutive features of its token straight from the page (no LDS).
-            // A wave scores 16 tokens per product group, the workgroup 64, two groups in flight.
-            constexpr int KST = D / 32, UM = 2;
-            const int row = lane & 15, dg = lane >> 4;
-            u32x4_t qh[KST], ql[KST];
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks) {
-                const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + min(row, G - 1)) * D + ks * 32 + dg * 8;
-                const float4 q0 = *reinterpret_cast<const float4 *>(qp);
-                const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
-                const float qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                uint16_t hh[8], ll[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) split_bf16(row < G ? qv[j] : 0.f, hh[j], ll[j]);
-                qh[ks] = u32x4_t{(uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16),
-                                 (uint32_t)hh[4] | ((uint32_t)hh[5] << 16), (uint32_t)hh[6] | ((uint32_t)hh[7] << 16)};
-                ql[ks] = u32x4_t{(uint32_t)ll[0] | ((uint32_t)ll[1] << 16), (uint32_t)ll[2] | ((uint32_t)ll[3] << 16),
-                                 (uint32_t)ll[4] | ((uint32_t)ll[5] << 16), (uint32_t)ll[6] | ((uint32_t)ll[7] << 16)};
-            }
-            const int64_t khead = (int64_t)h * P * D + dg * 8;
-            for (int r0 = 0; r0 < cnt; r0 += 64 * UM) {
-                u32x4_t kf[UM][KST];
-                int tl[UM];
-#pragma unroll
-                for (int u = 0; u < UM; ++u) {
-                    tl[u] = r0 + u * 64 + wave * 16 + row;
-                    const int tc = t0 + min(tl[u], cnt - 1);
-                    int page;
-                    if (rec_pages) {
-                        const int j = tc / P - pfirst;
-                        page = j == 0 ? m1.x : j == 1 ? m1.y : j == 2 ? m1.z : m1.w;
-                    } else {
-                        page = pt[tc / P];
-                    }
-                    const uint16_t *kr = kbase + page * page_elems + khead + (int64_t)(tc % P) * D;
-#pragma unroll
-                    for (int ks = 0; ks < KST; ++ks) kf[u][ks] = *reinterpret_cast<const u32x4_t *>(kr + ks * 32);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int u = 0; u < UM; ++u) {
-                    floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < KST; ++ks) {
-                        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qh[ks]), __builtin_bit_cast(bf16x8_t, kf[u][ks]), sacc, 0, 0, 0);
-                        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ql[ks]), __builtin_bit_cast(bf16x8_t, kf[u][ks]), sacc, 0, 0, 0);
-                    }
-                    // result tile: this lane holds query heads (lane / 16) * 4 .. + 3 of token column lane % 16
-                    if (tl[u] < cnt) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int g = dg * 4 + j;
-                            if (g < G) sc[g * kMaxChunk + tl[u]] = sacc[j] * scale;
-                        }
-                    }
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- chunk maximum, probabilities, their sum (one wave per query head) ----
-        for (int g = wave; g < G; g += 4) {
-            float m = -INFINITY;
-            for (int t = lane; t < cnt; t += 64) m = fmaxf(m, sc[g * kMaxChunk + t]);
-            m = wave_max(m);
-            float l = 0.f;
-            for (int t = lane; t < cnt; t += 64) {
-                const float p = expf(sc[g * kMaxChunk + t] - m);
-                sc[g * kMaxChunk + t] = p;
-                l += p;
-            }
-            l = wave_sum(l);
-            if (lane == 0) { ml[2 * g] = m; ml[2 * g + 1] = l; }
-        }
-        __syncthreads();
-
-        // ---- sum_t p_t V_t ----
-        float acc[G][8];
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
-        for (int r0 = 0; r0 < cnt; r0 += TPR * UR) {
-            uint4 kv[UR];
-            bool ok[UR];
-            if (r0 == 0) {
-#pragma unroll
-                for (int u = 0; u < UR; ++u) { kv[u] = vfirst[u]; ok[u] = okv[u]; }
-            } else {
-                load_rows(vbase, r0, kv, ok);
-            }
-#pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                if (!ok[u]) continue;
-                const float v0 = bf16lo(kv[u].x), v1 = bf16hi(kv[u].x), v2 = bf16lo(kv[u].y), v3 = bf16hi(kv[u].y);
-                const float v4 = bf16lo(kv[u].z), v5 = bf16hi(kv[u].z), v6 = bf16lo(kv[u].w), v7 = bf16hi(kv[u].w);
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    const float p = sc[g * kMaxChunk + r0 + u * TPR + ts];
-                    acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
-                    acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
-                    acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
-                    acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
-                }
-            }
-        }
-        // token rows of one wave share `seg` at lane distance LPT, 2 LPT, ...
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float v = acc[g][j];
-#pragma unroll
-                for (int o = 32; o >= LPT; o >>= 1) v += __shfl_xor(v, o, 64);
-                acc[g][j] = v;
-            }
-        if (lane < LPT) {
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) red[(wave * G + g) * D + lane * 8 + j] = acc[g][j];
-        }
-        __syncthreads();
-        for (int e = tid; e < G * D; e += kAttnThreads) {
-            const int g = e / D, dd = e - g * D;
-            const float v = (red[(0 * G + g) * D + dd] + red[(1 * G + g) * D + dd]) +
-                            (red[(2 * G + g) * D + dd] + red[(3 * G + g) * D + dd]);
-            a.part_acc[((int64_t)ce * a.hq + h * G + g) * D + dd] = v;
-        }
-        if (tid < 2 * G) a.part_ml[((int64_t)ce * a.hq + h * G) * 2 + tid] = ml[tid];
-        __syncthreads();
-    }
-}
-
-// The same work item for G < 4 (no matrix products), as one pass: K and V rows of a round of
+// G < 4 query heads per KV head (no matrix products), one pass: K and V rows of a round of
 // tokens are requested together, one round ahead of the arithmetic, and every wave keeps an
 // online-softmax state (running maximum, denominator, weighted V sum) over its own token rows,
 // so nothing but the final combination of the four waves' states goes through LDS and no
@@ -403,6 +206,217 @@ __global__ __launch_bounds__(kAttnThreads) void attn_stream_kernel(AttnArgs a)
     }
 }
 
+// G >= 4 query heads per KV head, one pass.  A round is 64 tokens, 16 per wave.  Per round a wave
+//   * scores its 16 tokens against all G heads with 16x16x32 matrix products (query heads as the
+//     split-bf16 rows of the A operand, kept in LDS; the 16 K rows straight from the page as the B
+//     operand): lane (token = lane % 16, dg = lane / 16) then holds the scores of heads 4 dg .. 4 dg + 3,
+//   * updates the running maximum and denominator of those heads there (maximum over the 16 token
+//     lanes by shuffles), and hands exp(s - m) and the rescale factors to the V layout through a
+//     wave-private LDS area (LDS operations of one wave execute in order: no barrier),
+//   * accumulates p V on the vector ALU in the V layout (a V row = D/8 lanes x 16 bytes).
+// K and V of the next round are requested before the current round's arithmetic.  The 16 tokens of
+// a wave's round lie in one page (pages hold a multiple of 16 tokens, chunks start on multiples of
+// 64), so the page id is one scalar load per wave and round, taken a round before it is needed:
+// chunks can be as long as the host likes (an item's fixed cost, a chain of dependent loads of
+// about 9 us, is what bounds this kernel on a shard with one KV head).
+template <int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void attn_gqa_kernel(AttnArgs a)
+{
+    static_assert(G == 4 || G == 8, "one or two lane groups of four heads");
+    constexpr int KST = D / 32;                 // matrix k-steps over the head dimension
+    constexpr int FE = 4;                       // features per lane in the V layout (8 would double the accumulators)
+    constexpr int LPT = D / FE;                 // lanes per V row
+    constexpr int RW = 64 / LPT;                // V rows of one wave load
+    constexpr int UV = 16 / RW;                 // wave loads per round (16 tokens per wave)
+    constexpr int RT = 64;                      // tokens per round of the workgroup
+    __shared__ uint4 qfrag[2 * KST * 64];       // A operand: [hi | lo][k-step][lane]
+    __shared__ __align__(16) float pw[4][16 * G];   // per wave: weight of (token, head), head fastest
+    __shared__ __align__(16) float cw[4][G];        // per wave: rescale factor of the head's running sum
+    __shared__ float red[4 * G * D];
+    __shared__ float wml[4 * G * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row = lane & 15, dg = lane >> 4;  // score layout: token lane, head group
+    const int rg = lane / LPT, seg = lane % LPT;   // V layout: row of the wave load, feature segment
+    const int hkv = a.kv.hkv, P = a.kv.P;
+    const float scale = rsqrtf((float)D);
+    const uint16_t *kbase = a.kv.pool + a.kv.base(a.layer, 0);
+    const uint16_t *vbase = a.kv.pool + a.kv.base(a.layer, 1);
+    const int64_t page_elems = a.kv.page_elems();
+
+    for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+        const int ce = item / hkv, h = item - ce * hkv;
+        const int4 m0 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce];
+        const int b = __builtin_amdgcn_readfirstlane(m0.x), t0 = __builtin_amdgcn_readfirstlane(m0.y),
+                  cnt = __builtin_amdgcn_readfirstlane(m0.z);
+        const int slot = a.row_slot ? __builtin_amdgcn_readfirstlane(a.row_slot[b]) : b;
+        const int32_t *pt = a.page_table + (int64_t)slot * a.max_pages;
+        const int64_t head_base = (int64_t)h * P * D;
+        // page of the wave's 16 tokens of the round at r0 (past the chunk: of its last token, where the clamped rows are)
+        auto page_of = [&](int r0) -> int { return pt[(t0 + min(r0 + wave * 16, cnt - 1)) / P]; };
+        auto fetch = [&](int r0, int page, u32x4_t (&kf)[KST], uint2 (&vf)[UV]) {
+            const int64_t base = page * page_elems + head_base;
+            const uint16_t *kr = kbase + base + (int64_t)((t0 + min(r0 + wave * 16 + row, cnt - 1)) % P) * D + dg * 8;
+            int64_t vo[UV];
+#pragma unroll
+            for (int u = 0; u < UV; ++u) vo[u] = base + (int64_t)((t0 + min(r0 + wave * 16 + u * RW + rg, cnt - 1)) % P) * D + seg * FE;
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) kf[ks] = *reinterpret_cast<const u32x4_t *>(kr + ks * 32);
+#pragma unroll
+            for (int u = 0; u < UV; ++u) vf[u] = *reinterpret_cast<const uint2 *>(vbase + vo[u]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        u32x4_t kA[KST], kB[KST];
+        uint2 vA[UV], vB[UV];
+        int pgA = page_of(0), pgB = page_of(RT);
+        fetch(0, pgA, kA, vA);
+
+        // the A operand: wave ks builds k-step ks (rows G..15 are zero)
+        if (wave < KST) {
+            const float *qp = a.qkv + (int64_t)b * a.ldq + (h * G + min(row, G - 1)) * D + wave * 32 + dg * 8;
+            const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+            const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+            const float qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+            uint16_t hh[8], ll[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) split_bf16(row < G ? qv[j] * scale : 0.f, hh[j], ll[j]);
+            qfrag[wave * 64 + lane] = make_uint4((uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16),
+                                                 (uint32_t)hh[4] | ((uint32_t)hh[5] << 16), (uint32_t)hh[6] | ((uint32_t)hh[7] << 16));
+            qfrag[(KST + wave) * 64 + lane] = make_uint4((uint32_t)ll[0] | ((uint32_t)ll[1] << 16), (uint32_t)ll[2] | ((uint32_t)ll[3] << 16),
+                                                         (uint32_t)ll[4] | ((uint32_t)ll[5] << 16), (uint32_t)ll[6] | ((uint32_t)ll[7] << 16));
+        }
+        __syncthreads();
+
+        float M[4], den[4];                      // score layout: heads 4 dg + j of this lane's token column
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { M[j] = -INFINITY; den[j] = 0.f; }
+        float acc[G][FE];                         // V layout
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int j = 0; j < FE; ++j) acc[g][j] = 0.f;
+        const bool head_lane = dg * 4 < G;        // this lane's four heads exist
+
+        auto consume = [&](int r0, const u32x4_t (&kf)[KST], const uint2 (&vf)[UV]) {
+            floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) {
+                const u32x4_t qh = *reinterpret_cast<const u32x4_t *>(&qfrag[ks * 64 + lane]);
+                const u32x4_t ql = *reinterpret_cast<const u32x4_t *>(&qfrag[(KST + ks) * 64 + lane]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qh), __builtin_bit_cast(bf16x8_t, kf[ks]), sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ql), __builtin_bit_cast(bf16x8_t, kf[ks]), sacc, 0, 0, 0);
+            }
+            const bool ok = r0 + wave * 16 + row < cnt;
+            float p[4], corr[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float sj = ok ? sacc[j] : -INFINITY;
+                float mr = sj;
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) mr = fmaxf(mr, __shfl_xor(mr, o, 64));      // over the 16 token lanes
+                const float Mn = fmaxf(M[j], mr);
+                const bool any = Mn != -INFINITY;                       // some token of this wave seen so far
+                corr[j] = any ? expf(M[j] - Mn) : 1.f;                  // exp(-inf) = 0 on the first tokens
+                p[j] = any ? expf(sj - Mn) : 0.f;                       // exp(-inf) = 0 past the chunk
+                den[j] = den[j] * corr[j] + p[j];
+                M[j] = Mn;
+            }
+            if (head_lane) {
+                *reinterpret_cast<float4 *>(&pw[wave][row * G + dg * 4]) = make_float4(p[0], p[1], p[2], p[3]);
+                if (row == 0) *reinterpret_cast<float4 *>(&cw[wave][dg * 4]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
+            }
+            __builtin_amdgcn_wave_barrier();      // keeps the reads below after the writes; the LDS executes a wave's operations in order
+            float cg[G];
+#pragma unroll
+            for (int g4 = 0; g4 < G; g4 += 4) {
+                const float4 c4 = *reinterpret_cast<const float4 *>(&cw[wave][g4]);
+                cg[g4] = c4.x; cg[g4 + 1] = c4.y; cg[g4 + 2] = c4.z; cg[g4 + 3] = c4.w;
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int j = 0; j < FE; ++j) acc[g][j] *= cg[g];
+#pragma unroll
+            for (int u = 0; u < UV; ++u) {
+                const float v0 = bf16lo(vf[u].x), v1 = bf16hi(vf[u].x), v2 = bf16lo(vf[u].y), v3 = bf16hi(vf[u].y);
+                float pg[G];
+#pragma unroll
+                for (int g4 = 0; g4 < G; g4 += 4) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(&pw[wave][(u * RW + rg) * G + g4]);
+                    pg[g4] = p4.x; pg[g4 + 1] = p4.y; pg[g4 + 2] = p4.z; pg[g4 + 3] = p4.w;
+                }
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    acc[g][0] = fmaf(pg[g], v0, acc[g][0]); acc[g][1] = fmaf(pg[g], v1, acc[g][1]);
+                    acc[g][2] = fmaf(pg[g], v2, acc[g][2]); acc[g][3] = fmaf(pg[g], v3, acc[g][3]);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();      // the next round's weights are written after these reads
+        };
+
+        for (int r0 = 0; r0 < cnt; r0 += 2 * RT) {
+            const bool second = r0 + RT < cnt;
+            if (second) fetch(r0 + RT, pgB, kB, vB);
+            pgA = page_of(r0 + 2 * RT);
+            consume(r0, kA, vA);
+            if (second) {
+                if (r0 + 2 * RT < cnt) fetch(r0 + 2 * RT, pgA, kA, vA);
+                pgB = page_of(r0 + 3 * RT);
+                consume(r0 + RT, kB, vB);
+            }
+        }
+
+        // the wave's state: denominators over the 16 token lanes, weighted sums over the rows of a wave load
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) den[j] += __shfl_xor(den[j], o, 64);
+        if (head_lane && row == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wml[(wave * G + dg * 4 + j) * 2] = M[j]; wml[(wave * G + dg * 4 + j) * 2 + 1] = den[j]; }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int j = 0; j < FE; ++j) {
+                float v = acc[g][j];
+#pragma unroll
+                for (int o = 32; o >= LPT; o >>= 1) v += __shfl_xor(v, o, 64);
+                acc[g][j] = v;
+            }
+        if (lane < LPT) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int j = 0; j < FE; ++j) red[(wave * G + g) * D + lane * FE + j] = acc[g][j];
+        }
+        __syncthreads();
+        // the four waves' states in wave order; wave 0 always holds the chunk's first token
+        for (int e = tid; e < G * D + G; e += kAttnThreads) {
+            const int g = e < G * D ? e / D : e - G * D;
+            float mw[4], Mc = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mw[w] = wml[(w * G + g) * 2]; Mc = fmaxf(Mc, mw[w]); }
+            float sw[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sw[w] = mw[w] == -INFINITY ? 0.f : expf(mw[w] - Mc);
+            if (e < G * D) {
+                const int dd = e - g * D;
+                a.part_acc[((int64_t)ce * a.hq + h * G + g) * D + dd] =
+                    (red[(0 * G + g) * D + dd] * sw[0] + red[(1 * G + g) * D + dd] * sw[1]) +
+                    (red[(2 * G + g) * D + dd] * sw[2] + red[(3 * G + g) * D + dd] * sw[3]);
+            } else {
+                float *ml = a.part_ml + ((int64_t)ce * a.hq + h * G + g) * 2;
+                ml[0] = Mc;
+                ml[1] = (wml[(0 * G + g) * 2 + 1] * sw[0] + wml[(1 * G + g) * 2 + 1] * sw[1]) +
+                        (wml[(2 * G + g) * 2 + 1] * sw[2] + wml[(3 * G + g) * 2 + 1] * sw[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // One wave per (sequence, query head): lanes = D/8 feature segments x 64/(D/8) chunk lanes.
 // A chunk lane folds the chunks c = lane, lane + CL, ... in increasing order, then the chunk
 // lanes are combined pairwise in a fixed tree (online-softmax identity), so the result is
@@ -477,8 +491,8 @@ hipError_t launch_partial_d(const AttnArgs &a, int grid, hipStream_t s)
     switch (G) {
     case 1: attn_stream_kernel<D, 1><<<grid, kAttnThreads, 0, s>>>(a); break;
     case 2: attn_stream_kernel<D, 2><<<grid, kAttnThreads, 0, s>>>(a); break;
-    case 4: attn_partial_kernel<D, 4><<<grid, kAttnThreads, 0, s>>>(a); break;
-    case 8: attn_partial_kernel<D, 8><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 4: attn_gqa_kernel<D, 4><<<grid, kAttnThreads, 0, s>>>(a); break;
+    case 8: attn_gqa_kernel<D, 8><<<grid, kAttnThreads, 0, s>>>(a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

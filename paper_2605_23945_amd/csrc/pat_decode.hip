@@ -260,17 +260,29 @@ hipError_t gemm_groups(GemmArgs g, int mode, hipStream_t st)
 
 int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
 {
-    // largest chunk that still gives the chip a few work items per compute unit (measured: the
-    // one-pass kernel of G < 4 wants about 4 per unit, the matrix-score kernel of G >= 4, whose
-    // items are G times as much arithmetic per byte, about 2)
-    const int thr = c->sh.hq / c->sh.hkv >= 4 ? 512 : 1024;
+    auto count = [&](int C) { int64_t n = 0; for (int i = 0; i < c->live; ++i) n += (c->kv_len[i] + 1 + C - 1) / C; return n; };
+    if (c->sh.hq / c->sh.hkv >= 4) {
+        // The matrix-score kernel holds three workgroups per compute unit; an item alone takes about
+        // 7 us (a chain of dependent loads) + 2.3 us per round of 64 tokens (measured at chunk lengths
+        // 64 .. 1024): take the chunk length that minimises (waves of items over the chip) x (time of
+        // one item).  This rule picks the measured best length at live batches 1 .. 256.
+        const int64_t slots = 3 * 256;
+        int best = kMinChunk; int64_t best_n = 0; double best_cost = 0.0;
+        for (int C : {1024, 512, 256, 128, 64}) {
+            const int64_t n = count(C), items = n * c->sh.hkv;
+            const double cost = (double)((items + slots - 1) / slots) * (7.0 + 2.3 * (C / 64));
+            if (best_n == 0 || cost < best_cost) { best = C; best_n = n; best_cost = cost; }
+        }
+        *n_chunks = best_n;
+        return best;
+    }
+    // one-pass kernel of G < 4: the largest chunk that still gives the chip about four work items
+    // per compute unit (measured)
     int best = kMinChunk;
     int64_t best_n = 0;
     for (int C : {256, 128, 64}) {
-        int64_t n = 0;
-        for (int i = 0; i < c->live; ++i) n += (c->kv_len[i] + 1 + C - 1) / C;
-        best = C; best_n = n;
-        if (n * c->sh.hkv >= thr) break;
+        best = C; best_n = count(C);
+        if (best_n * c->sh.hkv >= 1024) break;
     }
     *n_chunks = best_n;
     return best;
