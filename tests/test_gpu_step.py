@@ -143,6 +143,14 @@ def test_grouped_query_shapes(hq, hkv, d):
     _rollout_parity(pi.shard_of(m, 1, 0), 4, (30, 300), [3, 3, 2, 3])
 
 
+@pytest.mark.parametrize("page_tokens", [64, 16])
+def test_grouped_query_many_long_sequences_use_long_chunks(page_tokens):
+    """One KV head, 8 query heads, 72 sequences of about 3000 cached tokens: more 256-token chunks than
+    the chip holds at once, so the host picks 512-token chunks (8 rounds per item, 8 or 32 pages each)."""
+    m = pi.ModelShape(1, 256, 8, 1, 128, 512, 512)
+    _sampled_rows_parity(pi.shard_of(m, 1, 0), 72, (2800, 3300), [0, 17, 71], steps=2, page_tokens=page_tokens)
+
+
 def test_long_context_many_chunks_and_ragged_batch():
     """Lengths spanning several attention chunks and pages with a ragged tail; batch 19 = two batch tiles."""
     m = pi.ModelShape(1, 256, 4, 2, 64, 512, 512)
@@ -281,10 +289,10 @@ def test_70b_gqa_tp8_shape_two_layers_sampled_rows():
     dec.close()
 
 
-def _sampled_rows_parity(shard, n, prompt_len, rows, steps=1, max_seq=None):
+def _sampled_rows_parity(shard, n, prompt_len, rows, steps=1, max_seq=None, page_tokens=64):
     pat = _pat()
     req = pi.rollout_requests(shard, n, prompt_len, steps=steps + 2)
-    dec = make_decoder(shard, n, (max_seq or prompt_len[1]) + steps + 8, int(req["kv_len"].sum()) + 64 * n + 256)
+    dec = make_decoder(shard, n, (max_seq or prompt_len[1]) + steps + 8, int(req["kv_len"].sum()) + 2 * page_tokens * n + 256, page_tokens)
     pat.admit_synthetic(dec, shard, req, DEV)
     odec = make_oracle_decoder(shard, layer_cache=False)
     oracle_admit(odec, shard, req, rows, steps + 2)
