@@ -417,6 +417,220 @@ __global__ __launch_bounds__(kAttnThreads) void attn_gqa_kernel(AttnArgs a)
     }
 }
 
+// Prefill: the same one-pass kernel with the 16 operand rows holding 16 / G consecutive positions of
+// ONE sequence times the G heads of a KV head, so that a K/V row fetched once serves 16 (position,
+// head) pairs instead of G.  An item is (block of positions, chunk of keys, KV head); row i sees
+// the keys up to its own position (causal), and writes its partial into its own chunk list, which
+// the merge kernel reads as for a decode row.
+template <int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void attn_prefill_kernel(AttnArgs a)
+{
+    static_assert(G == 1 || G == 2 || G == 4 || G == 8, "the 16 operand rows are 16 / G positions x G heads");
+    constexpr int NR = 16;                      // operand rows: row i = position i / G of the block, head i % G
+    constexpr int KST = D / 32;                 // matrix k-steps over the head dimension
+    constexpr int FE = 4;                       // features per lane in the V layout (8 would double the accumulators)
+    constexpr int LPT = D / FE;                 // lanes per V row
+    constexpr int RW = 64 / LPT;                // V rows of one wave load
+    constexpr int UV = 16 / RW;                 // wave loads per round (16 tokens per wave)
+    constexpr int RT = 64;                      // tokens per round of the workgroup
+    __shared__ uint4 qfrag[2 * KST * 64];       // A operand: [hi | lo][k-step][lane]
+    __shared__ __align__(16) float pw[4][16 * NR];  // per wave: weight of (token, operand row), row fastest
+    __shared__ __align__(16) float cw[4][NR];       // per wave: rescale factor of the row's running sum
+    __shared__ float red[4 * NR * D];
+    __shared__ float wml[4 * NR * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row = lane & 15, dg = lane >> 4;  // score layout: token lane, head group
+    const int rg = lane / LPT, seg = lane % LPT;   // V layout: row of the wave load, feature segment
+    const int hkv = a.kv.hkv, P = a.kv.P;
+    const float scale = rsqrtf((float)D);
+    const uint16_t *kbase = a.kv.pool + a.kv.base(a.layer, 0);
+    const uint16_t *vbase = a.kv.pool + a.kv.base(a.layer, 1);
+    const int64_t page_elems = a.kv.page_elems();
+
+    for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+        const int ce = item / hkv, h = item - ce * hkv;
+        // one record per (block of up to 16 / G consecutive positions of one sequence, chunk of its keys)
+        const int4 m0 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce];
+        const int4 m1 = reinterpret_cast<const int4 *>(a.chunk_meta)[2 * (int64_t)ce + 1];
+        const int row0 = __builtin_amdgcn_readfirstlane(m0.x), n = __builtin_amdgcn_readfirstlane(m0.y),
+                  slot = __builtin_amdgcn_readfirstlane(m0.z), pos0 = __builtin_amdgcn_readfirstlane(m0.w),
+                  t0 = __builtin_amdgcn_readfirstlane(m1.x);
+        const int cnt = min(a.chunk_tokens, pos0 + n - t0);           // keys of this chunk that the block's last row sees
+        const int32_t *pt = a.page_table + (int64_t)slot * a.max_pages;
+        const int64_t head_base = (int64_t)h * P * D;
+        // page of the wave's 16 tokens of the round at r0 (past the chunk: of its last token, where the clamped rows are)
+        auto page_of = [&](int r0) -> int { return pt[(t0 + min(r0 + wave * 16, cnt - 1)) / P]; };
+        auto fetch = [&](int r0, int page, u32x4_t (&kf)[KST], uint2 (&vf)[UV]) {
+            const int64_t base = page * page_elems + head_base;
+            const uint16_t *kr = kbase + base + (int64_t)((t0 + min(r0 + wave * 16 + row, cnt - 1)) % P) * D + dg * 8;
+            int64_t vo[UV];
+#pragma unroll
+            for (int u = 0; u < UV; ++u) vo[u] = base + (int64_t)((t0 + min(r0 + wave * 16 + u * RW + rg, cnt - 1)) % P) * D + seg * FE;
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) kf[ks] = *reinterpret_cast<const u32x4_t *>(kr + ks * 32);
+#pragma unroll
+            for (int u = 0; u < UV; ++u) vf[u] = *reinterpret_cast<const uint2 *>(vbase + vo[u]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        u32x4_t kA[KST], kB[KST];
+        uint2 vA[UV], vB[UV];
+        int pgA = page_of(0), pgB = page_of(RT);
+        fetch(0, pgA, kA, vA);
+
+        // the A operand: wave ks builds k-step ks; rows of positions past the block are zero
+        if (wave < KST) {
+            const int pi = row / G, g = row - pi * G;
+            const float *qp = a.qkv + (int64_t)(row0 + min(pi, n - 1)) * a.ldq + (h * G + g) * D + wave * 32 + dg * 8;
+            const float4 q0 = *reinterpret_cast<const float4 *>(qp);
+            const float4 q1 = *reinterpret_cast<const float4 *>(qp + 4);
+            const float qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+            uint16_t hh[8], ll[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) split_bf16(pi < n ? qv[j] * scale : 0.f, hh[j], ll[j]);
+            qfrag[wave * 64 + lane] = make_uint4((uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16),
+                                                 (uint32_t)hh[4] | ((uint32_t)hh[5] << 16), (uint32_t)hh[6] | ((uint32_t)hh[7] << 16));
+            qfrag[(KST + wave) * 64 + lane] = make_uint4((uint32_t)ll[0] | ((uint32_t)ll[1] << 16), (uint32_t)ll[2] | ((uint32_t)ll[3] << 16),
+                                                         (uint32_t)ll[4] | ((uint32_t)ll[5] << 16), (uint32_t)ll[6] | ((uint32_t)ll[7] << 16));
+        }
+        __syncthreads();
+
+        float M[4], den[4];                      // score layout: operand rows 4 dg + j of this lane's token column
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { M[j] = -INFINITY; den[j] = 0.f; }
+        float acc[NR][FE];                        // V layout
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < FE; ++j) acc[g][j] = 0.f;
+        int lastkey[4];                           // last key position each of this lane's rows may see (causal), -1: no such row
+#pragma unroll
+        for (int j = 0; j < 4; ++j) lastkey[j] = (dg * 4 + j) / G < n ? pos0 + (dg * 4 + j) / G : -1;
+
+        auto consume = [&](int r0, const u32x4_t (&kf)[KST], const uint2 (&vf)[UV]) {
+            floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) {
+                const u32x4_t qh = *reinterpret_cast<const u32x4_t *>(&qfrag[ks * 64 + lane]);
+                const u32x4_t ql = *reinterpret_cast<const u32x4_t *>(&qfrag[(KST + ks) * 64 + lane]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qh), __builtin_bit_cast(bf16x8_t, kf[ks]), sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ql), __builtin_bit_cast(bf16x8_t, kf[ks]), sacc, 0, 0, 0);
+            }
+            const int key = t0 + r0 + wave * 16 + row;           // position of this lane's token column
+            const bool in_chunk = r0 + wave * 16 + row < cnt;
+            float p[4], corr[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float sj = (in_chunk && key <= lastkey[j]) ? sacc[j] : -INFINITY;
+                float mr = sj;
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) mr = fmaxf(mr, __shfl_xor(mr, o, 64));      // over the 16 token lanes
+                const float Mn = fmaxf(M[j], mr);
+                const bool any = Mn != -INFINITY;                       // some token of this wave seen so far
+                corr[j] = any ? expf(M[j] - Mn) : 1.f;                  // exp(-inf) = 0 on the first tokens
+                p[j] = any ? expf(sj - Mn) : 0.f;                       // exp(-inf) = 0 past the chunk
+                den[j] = den[j] * corr[j] + p[j];
+                M[j] = Mn;
+            }
+            *reinterpret_cast<float4 *>(&pw[wave][row * NR + dg * 4]) = make_float4(p[0], p[1], p[2], p[3]);
+            if (row == 0) *reinterpret_cast<float4 *>(&cw[wave][dg * 4]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
+            __builtin_amdgcn_wave_barrier();      // keeps the reads below after the writes; the LDS executes a wave's operations in order
+            float cg[NR];
+#pragma unroll
+            for (int g4 = 0; g4 < NR; g4 += 4) {
+                const float4 c4 = *reinterpret_cast<const float4 *>(&cw[wave][g4]);
+                cg[g4] = c4.x; cg[g4 + 1] = c4.y; cg[g4 + 2] = c4.z; cg[g4 + 3] = c4.w;
+            }
+#pragma unroll
+            for (int g = 0; g < NR; ++g)
+#pragma unroll
+                for (int j = 0; j < FE; ++j) acc[g][j] *= cg[g];
+#pragma unroll
+            for (int u = 0; u < UV; ++u) {
+                const float v0 = bf16lo(vf[u].x), v1 = bf16hi(vf[u].x), v2 = bf16lo(vf[u].y), v3 = bf16hi(vf[u].y);
+                float pg[NR];
+#pragma unroll
+                for (int g4 = 0; g4 < NR; g4 += 4) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(&pw[wave][(u * RW + rg) * NR + g4]);
+                    pg[g4] = p4.x; pg[g4 + 1] = p4.y; pg[g4 + 2] = p4.z; pg[g4 + 3] = p4.w;
+                }
+#pragma unroll
+                for (int g = 0; g < NR; ++g) {
+                    acc[g][0] = fmaf(pg[g], v0, acc[g][0]); acc[g][1] = fmaf(pg[g], v1, acc[g][1]);
+                    acc[g][2] = fmaf(pg[g], v2, acc[g][2]); acc[g][3] = fmaf(pg[g], v3, acc[g][3]);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();      // the next round's weights are written after these reads
+        };
+
+        for (int r0 = 0; r0 < cnt; r0 += 2 * RT) {
+            const bool second = r0 + RT < cnt;
+            if (second) fetch(r0 + RT, pgB, kB, vB);
+            pgA = page_of(r0 + 2 * RT);
+            consume(r0, kA, vA);
+            if (second) {
+                if (r0 + 2 * RT < cnt) fetch(r0 + 2 * RT, pgA, kA, vA);
+                pgB = page_of(r0 + 3 * RT);
+                consume(r0 + RT, kB, vB);
+            }
+        }
+
+        // the wave's state: denominators over the 16 token lanes, weighted sums over the rows of a wave load
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) den[j] += __shfl_xor(den[j], o, 64);
+        if (row == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wml[(wave * NR + dg * 4 + j) * 2] = M[j]; wml[(wave * NR + dg * 4 + j) * 2 + 1] = den[j]; }
+        }
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < FE; ++j) {
+                float v = acc[g][j];
+#pragma unroll
+                for (int o = 32; o >= LPT; o >>= 1) v += __shfl_xor(v, o, 64);
+                acc[g][j] = v;
+            }
+        if (lane < LPT) {
+#pragma unroll
+            for (int g = 0; g < NR; ++g)
+#pragma unroll
+                for (int j = 0; j < FE; ++j) red[(wave * NR + g) * D + lane * FE + j] = acc[g][j];
+        }
+        __syncthreads();
+        // the four waves' states in wave order.  A row takes part in this chunk when its position reaches
+        // the chunk's first key, which wave 0 then holds; its partial goes to the row's own chunk list.
+        for (int e = tid; e < NR * D + NR; e += kAttnThreads) {
+            const int i = e < NR * D ? e / D : e - NR * D;
+            const int pi = i / G, g = i - pi * G;
+            if (pi >= n || pos0 + pi < t0) continue;
+            const int64_t ci = a.chunk_start[row0 + pi] + t0 / a.chunk_tokens;
+            float mw[4], Mc = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mw[w] = wml[(w * NR + i) * 2]; Mc = fmaxf(Mc, mw[w]); }
+            float sw[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sw[w] = mw[w] == -INFINITY ? 0.f : expf(mw[w] - Mc);
+            if (e < NR * D) {
+                const int dd = e - i * D;
+                a.part_acc[(ci * a.hq + h * G + g) * D + dd] =
+                    (red[(0 * NR + i) * D + dd] * sw[0] + red[(1 * NR + i) * D + dd] * sw[1]) +
+                    (red[(2 * NR + i) * D + dd] * sw[2] + red[(3 * NR + i) * D + dd] * sw[3]);
+            } else {
+                float *ml = a.part_ml + (ci * a.hq + h * G + g) * 2;
+                ml[0] = Mc;
+                ml[1] = (wml[(0 * NR + i) * 2 + 1] * sw[0] + wml[(1 * NR + i) * 2 + 1] * sw[1]) +
+                        (wml[(2 * NR + i) * 2 + 1] * sw[2] + wml[(3 * NR + i) * 2 + 1] * sw[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+
 // One wave per (sequence, query head): lanes = D/8 feature segments x 64/(D/8) chunk lanes.
 // A chunk lane folds the chunks c = lane, lane + CL, ... in increasing order, then the chunk
 // lanes are combined pairwise in a fixed tree (online-softmax identity), so the result is
@@ -507,6 +721,29 @@ hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s)
     const int grid = a.n_items;          // one workgroup per item: measured faster than any capped grid with a loop
     if (a.kv.d == 128) return launch_partial_d<128>(a, grid, s);
     if (a.kv.d == 64) return launch_partial_d<64>(a, grid, s);
+    return hipErrorInvalidValue;
+}
+
+template <int D>
+static hipError_t launch_prefill_d(const AttnArgs &a, hipStream_t s)
+{
+    switch (a.hq / a.kv.hkv) {
+    case 1: attn_prefill_kernel<D, 1><<<a.n_items, kAttnThreads, 0, s>>>(a); break;
+    case 2: attn_prefill_kernel<D, 2><<<a.n_items, kAttnThreads, 0, s>>>(a); break;
+    case 4: attn_prefill_kernel<D, 4><<<a.n_items, kAttnThreads, 0, s>>>(a); break;
+    case 8: attn_prefill_kernel<D, 8><<<a.n_items, kAttnThreads, 0, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// a.chunk_meta holds block records (row0, rows, slot, first position | first key of the chunk), a.n_items = records x KV heads
+hipError_t launch_attn_prefill(const AttnArgs &a, hipStream_t s)
+{
+    if (a.n_items <= 0) return hipSuccess;
+    if (a.chunk_tokens > kMaxChunk || a.chunk_tokens <= 0 || a.chunk_tokens % 64) return hipErrorInvalidValue;
+    if (a.kv.d == 128) return launch_prefill_d<128>(a, s);
+    if (a.kv.d == 64) return launch_prefill_d<64>(a, s);
     return hipErrorInvalidValue;
 }
 

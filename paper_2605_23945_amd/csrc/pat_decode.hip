@@ -44,6 +44,7 @@ int64_t packed_w_bytes(int n, int k) { return (int64_t)cdiv(n, 16) * (k / 32) * 
 int64_t packed_x_bytes(int b, int k) { return (int64_t)cdiv(b, 16) * (k / 32) * 64 * 16; }
 
 const int kMinChunk = 64;
+const int kPfRecords = 32768;   // (block of positions, key chunk) records of one prefill pass
 
 }  // namespace
 
@@ -65,6 +66,7 @@ struct pat_ctx {
     int64_t step_index = 0;
     // pinned staging
     int32_t *pinned = nullptr;      // 6 * max_batch ints + report
+    int32_t *pf_stage = nullptr;    // pinned: block records of one prefill pass (kPfRecords x 8 ints)
     // timing
     bool timing = false;
     struct Ev { int klass; hipEvent_t a, b; };
@@ -329,9 +331,11 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
     const int MB = cfg->max_batch;
     c->seq_id.resize(MB); c->kv_len.resize(MB); c->gen.resize(MB); c->target.resize(MB); c->fin.assign(MB, 0);
     c->n_free = s.n_pages;
-    auto die = [&](const char *what, hipError_t e) { fprintf(stderr, "pat_decode_init: %s: %s\n", what, hipGetErrorString(e)); if (c->pinned) (void)hipHostFree(c->pinned); delete c; return PAT_EHIP; };
+    auto die = [&](const char *what, hipError_t e) { fprintf(stderr, "pat_decode_init: %s: %s\n", what, hipGetErrorString(e)); if (c->pinned) (void)hipHostFree(c->pinned); if (c->pf_stage) (void)hipHostFree(c->pf_stage); delete c; return PAT_EHIP; };
     hipError_t e = hipHostMalloc((void **)&c->pinned, (size_t)(7 * MB + 16) * 4, hipHostMallocDefault);
     if (e != hipSuccess) { c->pinned = nullptr; return die("hipHostMalloc", e); }
+    e = hipHostMalloc((void **)&c->pf_stage, (size_t)kPfRecords * 32, hipHostMallocDefault);
+    if (e != hipSuccess) { c->pf_stage = nullptr; return die("hipHostMalloc", e); }
     // rotary table: cos/sin of pos * base^(-2j/d) evaluated in double, stored as fp32 [pos][d/2][2]
     {
         const int half = s.d / 2, npos = cfg->max_seq_len + 1;
@@ -556,8 +560,10 @@ int pat_step_algo_bytes(pat_ctx *c, double *weight_bytes, double *kv_bytes)
 
 // The transformer layers over B rows whose embeddings sit in x: row b is the token at position pos[b]
 // (= tokens cached before it) of slot row_slot[b] (NULL: slot b, the decode step).  The attention
-// chunk records of these rows must have been planned.  Leaves the rows' final hidden states in x.
-static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t *pos, const int32_t *row_slot)
+// chunk records of these rows must have been planned; n_blocks > 0: the records are the block records
+// of a prefill pass (the block kernel), n_chunks still counts the rows' own chunks.  Leaves the rows'
+// final hidden states in x.
+static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t *pos, const int32_t *row_slot, int64_t n_blocks)
 {
     const Shard &s = c->sh;
     void *W = c->bufs.work;
@@ -593,7 +599,12 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
             }
         }
         aa.layer = l;
-        { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); PAT_HIP(c, launch_attn_merge(aa, st)); }
+        {
+            TimeScope t(c, 1);
+            if (n_blocks > 0) { aa.n_items = (int)(n_blocks * s.hkv); PAT_HIP(c, launch_attn_prefill(aa, st)); }
+            else PAT_HIP(c, launch_attn_partial(aa, st));
+            PAT_HIP(c, launch_attn_merge(aa, st));
+        }
         {
             GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
@@ -645,7 +656,7 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     { TimeScope t(c, 2); PAT_HIP(c, launch_plan_step(c->st, B, C, st)); }
     { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
 
-    if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr)) return rc;
+    if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr, 0)) return rc;
     { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
     {
         GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart);
@@ -707,25 +718,39 @@ int pat_prefill(pat_ctx *c, int32_t n, const int32_t *slots, const int32_t *toke
     char *Wb = at<char>(c->bufs.weights, 0);
     int si = 0, pos = 0;
     int64_t t = 0;
+    const int NP = 16 / (s.hq / s.hkv);            // positions per attention block (the kernel's 16 operand rows / heads per KV head)
+    int32_t *rec = c->pf_stage;
     while (t < n_tokens) {
         // one pass: the next rows in (slot, position) order, as many as the work buffers and the
-        // attention workspace take; a row's keys are rows of this or an earlier pass
+        // attention workspace take; a row's keys are rows of this or an earlier pass.  Rows of one
+        // sequence whose positions share pos / NP form a block; a block has one record per chunk of
+        // C keys up to its last position (C is a multiple of NP: every row of a block has the same chunks).
         int R = 0;
-        int64_t chunks = 0;
+        int64_t chunks = 0, n_rec = 0;
         while (R < R_max && t < n_tokens) {
             while (pos >= c->kv_len[slots[si]]) { ++si; pos = 0; }
             const int64_t need = (pos + 1 + C - 1) / C;
-            if (chunks + need > c->wl.max_chunks) break;
+            const bool new_block = R == 0 || p[MB + R - 1] != slots[si] || pos % NP == 0;
+            if (chunks + need > c->wl.max_chunks || (new_block && n_rec + need > kPfRecords)) break;
+            if (new_block) {
+                for (int64_t ch = 0; ch < need; ++ch) {
+                    int32_t *r8 = rec + (n_rec + ch) * 8;
+                    r8[0] = R; r8[1] = 0; r8[2] = slots[si]; r8[3] = pos; r8[4] = (int32_t)(ch * C); r8[5] = r8[6] = r8[7] = 0;
+                }
+                n_rec += need;
+            }
+            for (int64_t ch = 0; ch < need; ++ch) rec[(n_rec - need + ch) * 8 + 1] += 1;     // one more row in the current block
             p[R] = tokens[t]; p[MB + R] = slots[si]; p[2 * MB + R] = pos;
             chunks += need; ++R; ++t; ++pos;
         }
         if (R == 0) return fail(c, PAT_ENOMEM, "prefill: one row needs more attention chunks than the workspace holds");
         for (int a = 0; a < 3; ++a)
             PAT_HIP(c, hipMemcpyAsync(rows + a * MB, p + a * MB, (size_t)R * 4, hipMemcpyHostToDevice, c->stream));
-        PAT_HIP(c, launch_plan_rows(c->st, R, C, rows + MB, rows + 2 * MB, c->stream));
+        PAT_HIP(c, hipMemcpyAsync(c->st.chunk_meta, rec, (size_t)n_rec * 32, hipMemcpyHostToDevice, c->stream));
+        PAT_HIP(c, launch_plan_rows(c->st, R, C, rows + MB, rows + 2 * MB, false, c->stream));
         PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, rows, R, at<float>(W, c->wl.x), c->stream));
-        if (int rc = run_layers(c, R, C, chunks, rows + 2 * MB, rows + MB)) return rc;
-        PAT_HIP(c, hipStreamSynchronize(c->stream));     // the staging buffer is reused by the next pass
+        if (int rc = run_layers(c, R, C, chunks, rows + 2 * MB, rows + MB, n_rec)) return rc;
+        PAT_HIP(c, hipStreamSynchronize(c->stream));     // the staging buffers are reused by the next pass
     }
     return PAT_OK;
 }
@@ -883,6 +908,7 @@ int pat_decode_destroy(pat_ctx *c)
     for (auto &p : c->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     for (auto &p : c->ev_pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
     if (c->pinned) (void)hipHostFree(c->pinned);
+    if (c->pf_stage) (void)hipHostFree(c->pf_stage);
     delete c;
     return PAT_OK;
 }

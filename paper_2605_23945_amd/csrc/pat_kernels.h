@@ -72,6 +72,7 @@ struct AttnArgs {
     int n_items;               // n_chunks_total * hkv (host mirror)
 };
 hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_prefill(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s);
 
 // ---- small kernels (step_misc.hip) ----------------------------------------------
@@ -92,7 +93,7 @@ hipError_t launch_pool_init(const StateArrays &st, int n_pages, hipStream_t s);
 hipError_t launch_admit(const StateArrays &st, int live, int n, hipStream_t s);   // new slots' arrays already copied in
 hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipStream_t s);
 // chunk records for rows that are not slots (prefill): row i is position row_pos[i] of slot row_slot[i]
-hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, hipStream_t s);
+hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, bool write_records, hipStream_t s);
 hipError_t launch_embed(const uint16_t *table, int H, const int32_t *tok, int B, float *x, hipStream_t s);
 hipError_t launch_argmax(const float *logits, int B, int n, int base, int32_t *out_idx, float *out_val, hipStream_t s);
 hipError_t launch_finish(const StateArrays &st, const int32_t *next_tok, int B, int eos, void *report_dev, hipStream_t s);

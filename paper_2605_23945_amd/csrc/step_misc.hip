@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kBlk) void plan_step_kernel(StateArrays st, int B, 
 // at position row_pos[i] of slot row_slot[i], attending to positions 0 .. row_pos[i]).  No pages are
 // taken: the slots own the pages of their whole context since admission.
 __global__ __launch_bounds__(kBlk) void plan_rows_kernel(StateArrays st, int R, int C, const int32_t *row_slot,
-                                                         const int32_t *row_pos)
+                                                         const int32_t *row_pos, int write_records)
 {
     __shared__ int s_start[kBlk + 1];
     const int i = threadIdx.x;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kBlk) void plan_rows_kernel(StateArrays st, int R, 
     if (i < R) { st.chunk_start[i] = off_c; s_start[i] = off_c; }
     if (i == 0) { st.chunk_start[R] = tot_c; s_start[R] = tot_c; }
     __syncthreads();
-    const int n_rec = min(tot_c, st.max_chunks);
+    const int n_rec = write_records ? min(tot_c, st.max_chunks) : 0;     // 0: the caller supplies block records
     for (int ce = i; ce < n_rec; ce += kBlk) {
         int lo = 0, hi = R;
         while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_start[mid] <= ce) lo = mid; else hi = mid; }
@@ -378,10 +378,10 @@ hipError_t launch_plan_step(const StateArrays &st, int B, int chunk_tokens, hipS
     return hipGetLastError();
 }
 
-hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, hipStream_t s)
+hipError_t launch_plan_rows(const StateArrays &st, int R, int chunk_tokens, const int32_t *row_slot, const int32_t *row_pos, bool write_records, hipStream_t s)
 {
     if (R <= 0 || R > kBlk) return hipErrorInvalidValue;
-    plan_rows_kernel<<<1, kBlk, 0, s>>>(st, R, chunk_tokens, row_slot, row_pos);
+    plan_rows_kernel<<<1, kBlk, 0, s>>>(st, R, chunk_tokens, row_slot, row_pos, write_records ? 1 : 0);
     return hipGetLastError();
 }
 
