@@ -96,6 +96,12 @@ def test_tiny_long_sequence_spanning_passes_and_chunks():
     _prefill_parity(shard, [300, 270], [0, 1], max_batch=256)
 
 
+def test_pass_wider_than_one_projection_group():
+    """Pass width 320: a pass of 320 rows runs its projections as groups of 256 + 64 rows."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    _prefill_parity(shard, [200, 150, 90], [0, 1, 2], max_batch=320, page_tokens=16)
+
+
 @pytest.mark.parametrize("tp,rank", [(2, 1)])
 def test_tp_shard_prefill(tp, rank):
     shard = pi.ShardShape(pi.CONFIGS["tiny_tp1"]["shard"].model, tp, rank)

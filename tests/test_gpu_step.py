@@ -318,6 +318,13 @@ def test_7b_shape_two_layers_batch_200_full_batch_projections():
     _sampled_rows_parity(shard, 200, (64, 300), [0, 63, 64, 127, 128, 191, 192, 199], steps=2)
 
 
+def test_live_batch_300_runs_as_two_projection_groups():
+    """More than 256 live sequences: the projections run as groups of 256 rows (256 + 44 here), every
+    other kernel over all rows at once; rows on both sides of the group boundary are checked."""
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    _sampled_rows_parity(shard, 300, (10, 120), [0, 255, 256, 257, 299], steps=2, page_tokens=16)
+
+
 def test_13b_tp2_shard_batch_130_full_batch_projections():
     """Live batch 130 (nine batch tiles -> the 12-tile shape) on the hidden-5120 shard."""
     shard = pi.CONFIGS["13b_tp2"]["shard"].with_layers(2)
