@@ -278,13 +278,13 @@ int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
         *n_chunks = best_n;
         return best;
     }
-    // one-pass kernel of G < 4: the largest chunk that still gives the chip about four work items
-    // per compute unit (measured)
+    // one-pass kernel of G < 4 (measured at live batches 1 .. 256 on the 7B shard): 128-token chunks,
+    // 64 when that leaves fewer than two work items per compute unit; 256 is never faster
     int best = kMinChunk;
     int64_t best_n = 0;
-    for (int C : {256, 128, 64}) {
+    for (int C : {128, 64}) {
         best = C; best_n = count(C);
-        if (best_n * c->sh.hkv >= 1024) break;
+        if (best_n * c->sh.hkv >= 512) break;
     }
     *n_chunks = best_n;
     return best;
