@@ -329,7 +329,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
 // then low halves), the next group requested before the current one is multiplied
 #define PAT_XB_MUL(u_, wcur_)                                                                    \
     if (n_live > 0) {                                                                            \
-        constexpr int G = RA * RBT >= 32 ? 2 : (RBT < 4 ? RBT : 4), NG = 2 * RBT / G;           \
+        constexpr int G = (RA * RBT >= 32 || RBT % 4) ? 2 : 4, NG = 2 * RBT / G;           \
         const uint4 *buf = xs + ((u_) & 1) * NV + (wc * RBT) * 64 + lane;                        \
         u32x4_t f[2][G];                                                                         \
         _Pragma("unroll") for (int j = 0; j < G; ++j) f[0][j] = ld16(buf + j * 64);              \
@@ -568,6 +568,7 @@ static XbShape xb_shape(int B)
 {
     if (B <= 64) return {4, 8, 1, 4, 2};
     if (B <= 128) return {8, 8, 2, 4, 4};
+    if (B <= 192) return {12, 8, 2, 6, 4};
     return {16, 8, 2, 8, 4};
 }
 
@@ -613,7 +614,8 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
     if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
     const hipError_t e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s)
-                       : p.NB == 8 ? launch_xb<8, 2, 4, 4, 4>(a, mode, s) : launch_xb<8, 2, 8, 4, 2>(a, mode, s);
+                       : p.NB == 8 ? launch_xb<8, 2, 4, 4, 4>(a, mode, s)
+                       : p.NB == 12 ? launch_xb<8, 2, 6, 4, 2>(a, mode, s) : launch_xb<8, 2, 8, 4, 2>(a, mode, s);
     if (e != hipSuccess || a.Kb == 1) return e;
     const int64_t n = (int64_t)a.B * a.n_tiles * 4;
     const unsigned blocks = (unsigned)((n + 255) / 256);

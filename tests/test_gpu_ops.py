@@ -58,7 +58,7 @@ def test_weight_packing_and_mfma_layout_exact(pat):
 @pytest.mark.parametrize("n,k,b", [(256, 1024, 1), (256, 1024, 5), (1040, 352, 16), (512, 2752, 17), (96, 4096, 33),
                                    (64, 256, 100), (48, 64, 256), (4096, 4096, 8), (16, 32, 3),
                                    (4096, 1024, 200), (528, 2752, 130), (1024, 4096, 40), (256, 8192, 30),
-                                   (4096, 4096, 256), (2048, 11008, 96), (8192, 512, 192), (16384, 1024, 255),
+                                   (4096, 4096, 256), (2048, 11008, 96), (8192, 512, 192), (16384, 1024, 255), (4096, 4096, 177),
                                    (34000, 512, 250), (4112, 1024, 65), (22016, 1024, 129),
                                    (4096, 4096, 1), (4096, 11008, 2), (1040, 352, 2), (2064, 4096, 2), (16, 32, 1), (48, 64, 2),
                                    (8192, 28672, 1)])
