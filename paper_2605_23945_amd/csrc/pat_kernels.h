@@ -64,7 +64,8 @@ struct AttnArgs {
     const int32_t *row_slot;   // slot of batch row b, or NULL: slot b
     int max_pages;
     const int32_t *chunk_start;// [B + 1] exclusive prefix of per-slot chunk counts
-    const int32_t *chunk_meta; // [n_chunks_total][8] written by plan_step (see StateArrays)
+    const int32_t *chunk_meta; // [n_chunks_total][8] written by plan_step (see StateArrays); for launch_attn_prefill:
+                               // block records (first row, rows, slot, first position | first key of the chunk, -, -, -)
     int chunk_tokens;
     float *part_acc;           // [n_chunks_total][hq][d]
     float *part_ml;            // [n_chunks_total][hq][2]  (max, sum)
