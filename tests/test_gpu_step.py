@@ -368,6 +368,16 @@ def test_7b_full_depth_sampled_rows_in_bench_configuration():
     dec.close()
 
 
+@pytest.mark.parametrize("config,n,rows", [("70b_tp8", 40, [0, 39]), ("13b_tp2", 20, [3, 19])])
+def test_full_depth_shards_sampled_rows(config, n, rows):
+    """The 70B TP=8 shard (80 layers, 8 query heads on 1 KV head: the matrix-score attention kernel) and
+    the 13B TP=2 shard (40 layers) at full depth: oracle on two sampled rows, one step; the error after
+    80 layers must still meet the logit bar."""
+    shard = pi.CONFIGS[config]["shard"]
+    worst = _sampled_rows_parity(shard, n, (128, 700), rows, steps=1)
+    print(f"{config} full depth: worst {worst:.2e} x scale")
+
+
 def test_profile_grid_protocol():
     """Offline-profiler sweep: B*L <= T_cap pruning, row order, mean of the timed steps, byte model."""
     shard = pi.CONFIGS["tiny_tp1"]["shard"]
