@@ -211,6 +211,21 @@ int pat_profile_grid(pat_ctx *ctx, const int32_t *batches, int32_t nb, const int
                      int64_t t_cap, int32_t steps, int32_t warmup, int32_t reps, uint64_t seed,
                      pat_grid_row *rows_out, int32_t *n_rows);
 
+/* Prefill half of the offline profiler (Sec. 4.2, Eq. (4): the recomputation cost is read from profiled
+ * prefill latencies T_prefill(TP, batch, length)).  For every (batch, length) pair: resets the batch, admits
+ * `batch` sequences of `length` cached positions, rebuilds their states with pat_prefill from token ids
+ * drawn from `seed` (one untimed call, then `reps` timed ones, HIP events on the stream; the call's own
+ * waits between passes are inside the figure) and writes one row {tp_degree, batch, length, mean latency in
+ * microseconds}.  Pairs with batch * length > t_cap, or that do not fit max_batch / max_seq_len / the pool,
+ * get latency_us = -1.  rows_out (host) must hold nb * nl rows; row order is batch-major.  Leaves the batch
+ * empty. */
+typedef struct pat_prefill_row {
+    int32_t tp_degree, batch, length;
+    double  latency_us;
+} pat_prefill_row;
+int pat_profile_prefill(pat_ctx *ctx, const int32_t *batches, int32_t nb, const int32_t *lengths, int32_t nl, int64_t t_cap,
+                        int32_t reps, uint64_t seed, pat_prefill_row *rows_out);
+
 /* Drops every live sequence and returns all pages to the pool. */
 int pat_decode_reset(pat_ctx *ctx);
 

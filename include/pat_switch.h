@@ -56,11 +56,8 @@ int pat_predictor_line(const pat_predictor *p, int32_t tp, int32_t batch, double
  * profiled for tp or batch < 1. */
 int pat_predictor_query(const pat_predictor *p, int32_t tp, int32_t batch, double sum_context, double *latency_us);
 
-/* Profiled prefill latencies for the recomputation estimate: one row per (tp, batch, length). */
-typedef struct pat_prefill_row {
-    int32_t tp_degree, batch, length;
-    double  latency_us;
-} pat_prefill_row;
+/* pat_prefill_row, the profiled prefill latencies of the recomputation estimate, is declared in pat_decode.h
+ * (pat_profile_prefill measures them). */
 
 /* Everything one evaluation of Algorithm 1's loop body reads. */
 typedef struct pat_switch_input {

@@ -80,7 +80,7 @@ class pat_switch_decision(C.Structure):
 
 EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_layer_from_full", "pat_load_final", "pat_decode_admit",
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
-           "pat_profile_grid", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
+           "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
            "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
@@ -115,6 +115,7 @@ def load_library() -> C.CDLL:
     lib.pat_get_pages.argtypes = [vp, i32p, i32p, i32p]
     lib.pat_profile_grid.argtypes = [vp, i32p, C.c_int32, i32p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                      C.c_uint64, C.POINTER(pat_grid_row), i32p]
+    lib.pat_profile_prefill.argtypes = [vp, i32p, C.c_int32, i32p, C.c_int32, C.c_int64, C.c_int32, C.c_uint64, C.POINTER(pat_prefill_row)]
     lib.pat_decode_reset.argtypes = [vp]
     lib.pat_step_algo_bytes.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.pat_timing_enable.argtypes = [vp, C.c_int32]
@@ -303,6 +304,13 @@ class Decoder:
         self._chk(self.lib.pat_profile_grid(self.ctx, bp, len(b), lp, len(l), t_cap, steps, warmup, reps, seed, rows,
                                             C.byref(n)))
         return [{f: getattr(rows[i], f) for f, _ in pat_grid_row._fields_} for i in range(n.value)]
+
+    def pat_profile_prefill(self, batches, lengths, t_cap, reps=2, seed=1):
+        """Returns the ctypes array of pat_prefill_row (what pat_switch_decide takes) and the same rows as dicts."""
+        b, bp = _i32(batches); l, lp = _i32(lengths)
+        rows = (pat_prefill_row * (len(b) * len(l)))()
+        self._chk(self.lib.pat_profile_prefill(self.ctx, bp, len(b), lp, len(l), t_cap, reps, seed, rows))
+        return rows, [{f: getattr(rows[i], f) for f, _ in pat_prefill_row._fields_} for i in range(len(rows))]
 
     def pat_decode_reset(self):
         self._chk(self.lib.pat_decode_reset(self.ctx))

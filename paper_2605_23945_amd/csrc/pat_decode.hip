@@ -882,6 +882,50 @@ int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32
     return rc;
 }
 
+int pat_profile_prefill(pat_ctx *c, const int32_t *batches, int32_t nb, const int32_t *lengths, int32_t nl, int64_t t_cap,
+                        int32_t reps, uint64_t seed, pat_prefill_row *rows)
+{
+    if (!c) return PAT_EINVAL;
+    if (!batches || !lengths || !rows || nb <= 0 || nl <= 0 || reps <= 0) return fail(c, PAT_EINVAL, "profile_prefill: bad arguments");
+    const Shard &s = c->sh;
+    const int P = c->cfg.page_tokens;
+    hipEvent_t e0, e1;
+    PAT_HIP(c, hipEventCreate(&e0));
+    PAT_HIP(c, hipEventCreate(&e1));
+    std::vector<int32_t> ids, last, lens, tgts, slots, toks;
+    int rc = PAT_OK, r = 0;
+    for (int ib = 0; ib < nb && rc == PAT_OK; ++ib)
+        for (int il = 0; il < nl && rc == PAT_OK; ++il, ++r) {
+            const int B = batches[ib], L = lengths[il];
+            rows[r] = pat_prefill_row{c->cfg.tp_degree, B, L, -1.0};
+            if (B <= 0 || L <= 0) { rc = fail(c, PAT_EINVAL, "profile_prefill: batch %d / length %d", B, L); break; }
+            if ((int64_t)B * L > t_cap || B > c->cfg.max_batch || L + 1 > c->cfg.max_seq_len ||
+                (int64_t)B * cdiv(L + 1, P) > s.n_pages) continue;
+            ids.resize(B); last.assign(B, 0); lens.assign(B, L); tgts.assign(B, 1); slots.resize(B);
+            toks.resize((size_t)B * L);
+            uint64_t x = seed ^ ((uint64_t)B << 32) ^ (uint64_t)L;
+            for (size_t i = 0; i < toks.size(); ++i) {          // splitmix64: token ids uniform over the vocabulary
+                x += 0x9E3779B97F4A7C15ull;
+                uint64_t z = x; z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull; z = (z ^ (z >> 27)) * 0x94D049BB133111EBull; z ^= z >> 31;
+                toks[i] = (int32_t)(z % (uint64_t)s.V);
+            }
+            for (int i = 0; i < B; ++i) { ids[i] = i; slots[i] = i; }
+            if ((rc = pat_decode_reset(c)) != PAT_OK) break;
+            if ((rc = pat_decode_admit(c, B, ids.data(), last.data(), lens.data(), tgts.data())) != PAT_OK) break;
+            if ((rc = pat_prefill(c, B, slots.data(), toks.data(), (int64_t)toks.size())) != PAT_OK) break;      // untimed
+            if (hipEventRecord(e0, c->stream) != hipSuccess) { rc = fail(c, PAT_EHIP, "event record"); break; }
+            for (int rep = 0; rep < reps && rc == PAT_OK; ++rep) rc = pat_prefill(c, B, slots.data(), toks.data(), (int64_t)toks.size());
+            if (rc != PAT_OK) break;
+            if (hipEventRecord(e1, c->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { rc = fail(c, PAT_EHIP, "event sync"); break; }
+            float ms = 0.f;
+            (void)hipEventElapsedTime(&ms, e0, e1);
+            rows[r].latency_us = 1e3 * ms / reps;
+        }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (rc == PAT_OK) rc = pat_decode_reset(c);
+    return rc;
+}
+
 int pat_timing_enable(pat_ctx *c, int32_t on)
 {
     if (!c) return PAT_EINVAL;

@@ -4,10 +4,10 @@ recomputation estimate of the switch decision interpolates (Eq. (4)).
     python -m paper_2605_23945_amd.prefill_bench [--config 7b_tp1] [--layers N] [--batch 1,4,16] [--len 256,1024,4096]
                                                  [--pass-width 256] [--reps 2]
 
-For each (batch, length): admits `batch` sequences of `length` positions (page contents are whatever the
-pool holds; the prefill overwrites them), rebuilds their K/V from seeded token ids with pat_prefill and
-times the call with HIP events on the launch stream (the call waits for the GPU after every pass, so
-the host time between passes is inside the figure).  Prints one JSON object; `rows` holds the table in
+Calls pat_profile_prefill: for each (batch, length) it admits `batch` sequences of `length` positions (page
+contents are whatever the pool holds; the prefill overwrites them), rebuilds their K/V from seeded token ids
+with pat_prefill and times the call with HIP events on the launch stream (the call waits for the GPU after
+every pass, so the host time between passes is inside the figure).  Prints one JSON object; `rows` holds the table in
 the layout of pat_prefill_row.  flops = 2 x projection weights x tokens + the causal attention's
 4 x hq x d x length^2 / 2 per sequence and layer; the fraction is against the dense bf16 MFMA peak.
 """
@@ -47,26 +47,17 @@ def main():
     m = shard.model
     per_tok = 2.0 * shard.n_layers * (shard.hidden * (shard.hq + 2 * shard.hkv) * m.head_dim + shard.hidden * shard.hq * m.head_dim
                                       + 3 * shard.hidden * shard.ffn)
+    _, prof = dec.pat_profile_prefill(bs, ls, 1 << 40, reps=args.reps)
     rows = []
-    for b in bs:
-        for L in ls:
-            dec.pat_decode_reset()
-            dec.pat_decode_admit(np.arange(b, dtype=np.int32), np.zeros(b, np.int32), np.full(b, L, np.int32), np.full(b, 4, np.int32))
-            toks = np.concatenate([pi.prompt_tokens(shard, i, L) for i in range(b)])
-            slots = list(range(b))
-            dec.pat_prefill(slots, toks)                                      # warm-up
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.reps):
-                dec.pat_prefill(slots, toks)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / args.reps
-            flops = per_tok * b * L + shard.n_layers * b * 4.0 * shard.hq * m.head_dim * L * (L + 1) / 2
-            rows.append({"tp_degree": shard.tp, "batch": b, "length": L, "latency_us": round(us, 1),
-                         "tokens_per_s": round(b * L / us * 1e6, 1), "passes": -(-b * L // width),
-                         "tflops": round(flops / us * 1e-6, 2), "frac_of_bf16_mfma_peak": round(flops / us * 1e6 / MFMA_BF16_PEAK, 4)})
-            print(f"batch {b} length {L}: {us / 1e3:.1f} ms", file=sys.stderr, flush=True)
+    for r in prof:
+        b, L, us = r["batch"], r["length"], r["latency_us"]
+        if us < 0:
+            rows.append({"tp_degree": shard.tp, "batch": b, "length": L, "latency_us": None})
+            continue
+        flops = per_tok * b * L + shard.n_layers * b * 4.0 * shard.hq * m.head_dim * L * (L + 1) / 2
+        rows.append({"tp_degree": shard.tp, "batch": b, "length": L, "latency_us": round(us, 1),
+                     "tokens_per_s": round(b * L / us * 1e6, 1), "passes": -(-b * L // width),
+                     "tflops": round(flops / us * 1e-6, 2), "frac_of_bf16_mfma_peak": round(flops / us * 1e6 / MFMA_BF16_PEAK, 4)})
     print(json.dumps({"config": args.config, "tp_degree": shard.tp, "n_layers": shard.n_layers, "pass_width": width, "rows": rows}))
     dec.close()
 

@@ -151,3 +151,32 @@ def test_error_paths_change_nothing():
         for l in range(shard.n_layers):
             assert np.array_equal(got[l][0], before[j][l][0]) and np.array_equal(got[l][1], before[j][l][1])
     dec.close()
+
+
+def test_profile_prefill_table_feeds_the_switch_decision():
+    """The prefill half of the offline profiler: row order, skipped points, a latency that grows with the
+    work, an empty batch afterwards; the rows serve as the T_prefill table of the switch decision, whose
+    recomputation cost then equals the profiled latency at a profiled point."""
+    pat = _pat()
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    dec = make_decoder(shard, 64, 600, 8 * 600 + 64 * 64, 16)
+    arr, rows = dec.pat_profile_prefill([1, 4, 8], [64, 512, 1024], 4 * 512, reps=2)
+    assert [(r["batch"], r["length"]) for r in rows] == [(b, L) for b in (1, 4, 8) for L in (64, 512, 1024)]
+    assert all(r["tp_degree"] == 1 for r in rows)
+    lat = {(r["batch"], r["length"]): r["latency_us"] for r in rows}
+    assert lat[(8, 512)] == -1.0                    # 8 * 512 tokens exceed the token cap
+    assert all(lat[(b, 1024)] == -1.0 for b in (1, 4, 8))   # longer than max_seq_len
+    for key in ((1, 64), (1, 512), (4, 64), (4, 512), (8, 64)):
+        assert lat[key] > 0.0
+    assert lat[(4, 512)] > lat[(4, 64)] and lat[(4, 512)] > lat[(1, 512)]
+    assert dec.pat_get_state()["live"] == 0 and len(dec.pat_get_pages()[1]) == dec.req.n_pages
+    dec.close()
+    # Algorithm 1 with this table: four unfinished samples of length 512 restored on one TP=1 group of a
+    # one-GPU "node"; recomputation is looked up at the profiled point (batch 4, length 512) itself
+    grid = [(tp, b, T, 1000.0 + 0.01 * T) for tp in (1, 2) for b in (1, 4) for T in (100, 4000)]
+    pred = pat.Predictor(grid)
+    table = [(2, r["batch"], r["length"], r["latency_us"]) for r in rows if r["latency_us"] > 0]
+    out = pred.pat_switch_decide(1, [1, 2], [(2, 1024.0), (2, 1024.0)], 600, 100, [512] * 4, (2, 256, 2),
+                                 {(1, 2): 0.0}, 1.0, 2, prefill=table)     # 1 byte/s network: migration is out
+    t_switch = dict((tp, sw) for tp, _, sw, _ in out[4])[2]
+    assert t_switch == pytest.approx(lat[(4, 512)], rel=1e-12)
