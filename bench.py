@@ -38,7 +38,7 @@ def plan_rollout(req):
     return steps, peak
 
 
-def cpu_baseline(shard, req, host_layers, final_w, n_rows=2):
+def cpu_baseline(shard, req, host_layers, final_w, n_rows=8):
     """Times the CPU oracle (as it stands) on a bounded sample: one full-depth decode step of
     `n_rows` sequences of the workload (those with the median prompt lengths)."""
     import pat_inputs as pi
