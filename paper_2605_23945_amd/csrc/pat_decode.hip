@@ -55,6 +55,7 @@ struct pat_ctx {
     WeightLayout wt;
     pat_buffers bufs;
     hipStream_t stream;
+    int n_cu = 256;                 // compute units of the device (MI355X: 256)
     KvLayout kv;
     StateArrays st;
     std::vector<char> layer_loaded;
@@ -268,7 +269,7 @@ int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
         // 7 us (a chain of dependent loads) + 2.3 us per round of 64 tokens (measured at chunk lengths
         // 64 .. 1024): take the chunk length that minimises (waves of items over the chip) x (time of
         // one item).  This rule picks the measured best length at live batches 1 .. 256.
-        const int64_t slots = 3 * 256;
+        const int64_t slots = 3 * (int64_t)c->n_cu;
         int best = kMinChunk; int64_t best_n = 0; double best_cost = 0.0;
         for (int C : {1024, 512, 256, 128, 64}) {
             const int64_t n = count(C), items = n * c->sh.hkv;
@@ -284,7 +285,7 @@ int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
     int64_t best_n = 0;
     for (int C : {128, 64}) {
         best = C; best_n = count(C);
-        if (best_n * c->sh.hkv >= 512) break;
+        if (best_n * c->sh.hkv >= 2 * (int64_t)c->n_cu) break;
     }
     *n_chunks = best_n;
     return best;
@@ -354,7 +355,7 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
     }
     {
         hipDeviceProp_t prop; int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) gemm_set_compute_units(prop.multiProcessorCount);
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) { gemm_set_compute_units(prop.multiProcessorCount); c->n_cu = prop.multiProcessorCount; }
     }
     e = launch_pool_init(c->st, s.n_pages, c->stream);
     if (e != hipSuccess) return die("pool init", e);
