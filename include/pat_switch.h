@@ -76,7 +76,9 @@ typedef struct pat_switch_input {
     const double *fixed_us;         /* [n_tp][n_tp] measured fixed cost from tp_list[i] to tp_list[j]
                                        (weight resharding, group update, control); the current degree
                                        must be in tp_list */
-    const pat_prefill_row *prefill; /* may be NULL */
+    const pat_prefill_row *prefill; /* may be NULL.  Rows with latency_us < 0 (or NaN) are pairs the profiler
+                                       did not measure and are ignored; a (tp, batch, length) measured twice is
+                                       PAT_EINVAL; a degree left without measured rows has no recomputation estimate */
     int32_t n_prefill;
 } pat_switch_input;
 

@@ -127,14 +127,23 @@ def rms_length(lengths):
 
 
 class PrefillTable:
-    """rows: (tp, batch, length, microseconds) of profiled prefill latencies (reading R5)."""
+    """rows: (tp, batch, length, microseconds) of profiled prefill latencies (reading R5).
+
+    Eq. (4) reads a PROFILED latency: a row whose latency is negative or NaN is how the profiler marks
+    a (batch, length) pair it did not measure (over the token cap, or not fitting the pool) and is no
+    point of any curve.  Two measured rows of one (tp, batch, length) are a malformed table."""
 
     def __init__(self, rows):
         self.curves = {}
         for tp, b, l, us in rows:
+            if not (float(us) >= 0.0):              # unmeasured marker (-1) or NaN
+                continue
             self.curves.setdefault((int(tp), int(b)), []).append((float(l), float(us)))
         for k in self.curves:
             self.curves[k].sort()
+            ls = [q[0] for q in self.curves[k]]
+            if len(set(ls)) != len(ls):
+                raise ValueError(f"prefill table: length profiled twice for (tp, batch) = {k}")
         self.batches = {}
         for tp, b in self.curves:
             self.batches.setdefault(tp, []).append(b)
@@ -152,6 +161,8 @@ class PrefillTable:
         return y0 + (y1 - y0) * (length - l0) / (l1 - l0)
 
     def query(self, tp, batch, length):
+        if tp not in self.batches:                  # nothing measured for this degree: recomputation unavailable
+            return math.inf
         bs = self.batches[tp]
         if batch <= bs[0]:
             return self.curve_value(tp, bs[0], length)

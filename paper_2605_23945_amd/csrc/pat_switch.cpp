@@ -183,14 +183,22 @@ int pat_switch_decide(const pat_predictor *p, const pat_switch_input *in, pat_sw
         sum_b += in->group_batch[g]; sum_t += in->group_context[g];
     }
 
-    // prefill curves of the recomputation estimate
+    // prefill curves of the recomputation estimate.  Eq. (4) reads a profiled latency: a row with a negative
+    // or NaN latency is the profiler's mark of a pair it did not measure and is no point of a curve; a
+    // (tp, batch) left without points has no curve, a degree left without curves no recomputation estimate.
     std::map<int32_t, ByBatch<Curve>> pre;
     if (in->n_prefill > 0) {
         std::map<std::pair<int32_t, int32_t>, Curve> c;
-        for (int32_t i = 0; i < in->n_prefill; ++i)
-            c[{in->prefill[i].tp_degree, in->prefill[i].batch}].push_back({(double)in->prefill[i].length, in->prefill[i].latency_us});
+        for (int32_t i = 0; i < in->n_prefill; ++i) {
+            const pat_prefill_row &r = in->prefill[i];
+            if (!(r.latency_us >= 0.0)) continue;
+            if (r.tp_degree < 1 || r.batch < 1 || r.length < 1) return PAT_EINVAL;
+            c[{r.tp_degree, r.batch}].push_back({(double)r.length, r.latency_us});
+        }
         for (auto &kv : c) {
             std::sort(kv.second.begin(), kv.second.end());
+            for (size_t i = 1; i < kv.second.size(); ++i)
+                if (kv.second[i].first == kv.second[i - 1].first) return PAT_EINVAL;    // a length measured twice
             ByBatch<Curve> &bb = pre[kv.first.first];
             bb.batch.push_back(kv.first.second);
             bb.val.push_back(kv.second);

@@ -112,3 +112,40 @@ def test_bad_inputs_are_rejected():
     for bad in (dict(tp=4), dict(tp_list=[2]), dict(n_gpus=3), dict(net_bytes_per_s=0.0), dict(tp_list=[1, 8])):
         with pytest.raises(pat.PatError):
             p.pat_switch_decide(**{**ok, **bad})
+
+
+def test_unmeasured_prefill_rows_do_not_change_decisions():
+    """A raw table as pat_profile_prefill writes it (latency -1 for pairs over the token cap or not
+    fitting) must give the decision of the table with those rows removed; the oracle says the same."""
+    rng = np.random.default_rng(41)
+    rows = _sweep(rng, noise=10.0)
+    o, p = oc.Predictor(rows), pat.Predictor(rows)
+    full = [(tp, b, L, 0.4 * b * L / tp + 2e-5 * b * L * L / tp) for tp in (1, 2, 4, 8) for b in (1, 4, 16, 64)
+            for L in (512, 2048, 8192, 32768)]
+    raw = [(tp, b, L, us if b * L <= 2 ** 17 else -1.0) for tp, b, L, us in full]       # the profiler's cap rule
+    raw += [(8, 128, 512, -1.0)]                                                         # a batch with no measured row at all
+    clean = [r for r in raw if r[3] >= 0]
+    assert 0 < len(clean) < len(raw)
+    n_recomp = 0
+    for case in range(120):
+        tp = int(rng.choice([1, 2, 4, 8]))
+        tp_list = [1, 2, 4, 8]
+        dp = 8 // tp
+        lens_per_group = [[int(x) for x in rng.integers(200, 30000, int(rng.integers(1, 5)))] for _ in range(dp)]
+        groups = [(len(g), float(sum(g))) for g in lens_per_group]
+        lengths = [x for g in lens_per_group for x in g]
+        fixed = {(a, b): (0.0 if a == b else float(rng.uniform(2e5, 4e6))) for a in tp_list for b in tp_list}
+        net = float(rng.uniform(0.2e9, 5e9))                     # slow links: recomputation often the cheaper
+        args = (tp, tp_list, groups, 9000, int(rng.integers(0, 8000)), lengths, (32, 4096, 2), fixed, net, 8)
+        a = p.pat_switch_decide(*args, raw)
+        b = p.pat_switch_decide(*args, clean)
+        ref = oc.decide(o, *args[:3], *args[3:], oc.PrefillTable(raw))
+        assert a == b, case
+        assert all(s >= 0.0 for _, _, s, _ in a[4]), case        # no cost pulled below zero by a -1 row
+        for (c0, r0, s0, t0), (c1, r1, s1, t1) in zip(ref[4], a[4]):
+            assert c0 == c1 and _close(s0, s1) and _close(t0, t1), (case, c0)
+        move = 1e6 * oc.kv_move_time(lengths, 32, 4096, 2, tp, net)
+        n_recomp += any(c != tp and s < fixed[(tp, c)] + move * (1 - 1e-12) for c, _, s, _ in a[4])
+    assert n_recomp > 20                                          # the recomputation branch was the minimum often enough
+    with pytest.raises(pat.PatError):                             # a (tp, batch, length) measured twice
+        p.pat_switch_decide(*args, clean + [clean[0]])

@@ -153,3 +153,87 @@ def test_algorithm_1_argmin_matches_brute_force():
             # remaining time is monotone in what it sums: never below steps x the cheapest step
             lo = min(p.query(cand, mb, mt), p.query(cand, mb, mt + (steps - 1) * mb))
             assert t_rem >= steps * lo * (1 - 1e-12)
+
+
+# ---- T_switch with a prefill table: Eq. (3)-(4) and min(T_move, T_recomp) of Sec. 4.2 ----------------
+# Mistakes these catch: the group batch of Eq. (4) taken as all samples instead of ceil(n / (G / tp')), the mean
+# length instead of the RMS, the source degree's table instead of the target's, max instead of min, the fixed
+# cost dropped or added twice, T_move in seconds added to microseconds.
+
+def test_switch_cost_recomputation_branch_hand_computed():
+    model = (32, 4096, 2)
+    fixed = {(1, 4): 7000.0, (4, 1): 9000.0, (1, 2): 100.0, (1, 1): 0.0, (4, 4): 0.0}
+    # target TP 4 on 8 GPUs: 2 DP groups; five unfinished samples -> ceil(5 / 2) = 3 per group
+    lengths = [1000, 1000, 2000, 2000, 4000]
+    l_rms = math.sqrt((2 * 1000 ** 2 + 2 * 2000 ** 2 + 4000 ** 2) / 5)          # 2280.35..., the mean is 2000
+    assert l_rms == pytest.approx(2280.350850198276, rel=1e-15)
+    rows = [(4, 2, 2000, 100.0), (4, 2, 3000, 200.0), (4, 4, 2000, 300.0), (4, 4, 3000, 500.0),
+            (1, 3, 2000, 1.0), (1, 3, 3000, 2.0)]                                # TP 1 rows: the wrong table if used
+    pf = oc.PrefillTable(rows)
+    at2 = 100.0 + 100.0 * (l_rms - 2000) / 1000                                   # batch 2 curve at L_RMS
+    at4 = 300.0 + 200.0 * (l_rms - 2000) / 1000                                   # batch 4 curve
+    t_recomp = 0.5 * at2 + 0.5 * at4                                              # batch 3: halfway
+    assert t_recomp == pytest.approx(200.0 + 150.0 * 0.280350850198276, rel=1e-12)
+    # migration at 1 GB/s: 2 * 32 * 10000 tokens * 4096 / 1 * 2 bytes = 5.24288e9 bytes -> 5.24288 s = 5 242 880 us
+    t_move_slow = 2 * 32 * 10000 * 4096 * 2 / 1e9 * 1e6
+    assert t_move_slow == pytest.approx(5242880.0)
+    # recomputation wins on a slow network
+    got = oc.switch_cost_us(1, 4, lengths, model, fixed, 1e9, pf, 8)
+    assert got == pytest.approx(7000.0 + t_recomp, rel=1e-12)
+    # migration wins on a fast one: 1e15 B/s -> 5.24288 us
+    got = oc.switch_cost_us(1, 4, lengths, model, fixed, 1e15, pf, 8)
+    assert got == pytest.approx(7000.0 + 5.24288, rel=1e-12)
+    # no table: migration whatever it costs; same degree: nothing
+    assert oc.switch_cost_us(1, 4, lengths, model, fixed, 1e9, None, 8) == pytest.approx(7000.0 + t_move_slow, rel=1e-12)
+    assert oc.switch_cost_us(4, 4, lengths, model, fixed, 1e9, pf, 8) == 0.0
+    # a target degree the table holds no row for (TP 2): recomputation unavailable, not an error
+    assert oc.switch_cost_us(1, 2, lengths, model, fixed, 1e9, pf, 8) == pytest.approx(100.0 + t_move_slow, rel=1e-12)
+    # the source degree divides the migration volume (Eq. (1)): from TP 4 it is a quarter
+    assert oc.switch_cost_us(4, 1, lengths, model, fixed, 1e9, None, 8) == pytest.approx(9000.0 + t_move_slow / 4, rel=1e-12)
+
+
+def test_switch_cost_at_a_profiled_point_equals_the_table_entry():
+    # equal lengths: L_RMS is that length; 8 samples onto TP 2 of 8 GPUs = 4 groups of 2: the (2, 2, 1024) entry itself
+    pf = oc.PrefillTable([(2, 1, 1024, 11.0), (2, 2, 512, 17.0), (2, 2, 1024, 31.0), (2, 2, 2048, 77.0), (2, 4, 1024, 59.0)])
+    fixed = {(8, 2): 5.0}
+    assert oc.switch_cost_us(8, 2, [1024] * 8, (4, 256, 2), fixed, 1.0, pf, 8) == pytest.approx(5.0 + 31.0, rel=1e-15)
+    # 7 samples still make groups of ceil(7 / 4) = 2; 9 samples make groups of 3: halfway between batch 2 and 4
+    assert oc.switch_cost_us(8, 2, [1024] * 7, (4, 256, 2), fixed, 1.0, pf, 8) == pytest.approx(5.0 + 31.0, rel=1e-15)
+    assert oc.switch_cost_us(8, 2, [1024] * 9, (4, 256, 2), fixed, 1.0, pf, 8) == pytest.approx(5.0 + 45.0, rel=1e-15)
+
+
+def test_decide_with_prefill_table_recomputation_and_migration_outcomes():
+    p = _toy()
+    model = (32, 4096, 2)
+    fixed = {(1, 4): 1.0e6, (1, 1): 0.0}
+    groups, lengths = [(1, 3000.0)] * 4, [3000] * 4
+    # 4 GPUs -> TP 4 is one group of all four samples at L_RMS = 3000: the (4, 4, 3000) entry
+    pf = oc.PrefillTable([(4, 4, 3000, 250000.0), (4, 4, 6000, 900000.0)])
+    move = 4 * 2 * 32 * 3000 * 4096 * 2 / 25e9 * 1e6                              # 251 658.24 us at 25 GB/s
+    assert move == pytest.approx(251658.24)
+    w = 3 / 63
+    rem4 = sum((1 - w) * (1500 + 5e-4 * (12000 + 4 * k)) + w * (12000 + 5e-4 * (12000 + 4 * k)) for k in range(1000))
+    do, tp_new, t_cur, t_best, totals = oc.decide(p, 1, [1, 4], groups, 4000, 3000, lengths, model, fixed, 25e9, 4, pf)
+    assert totals[1][2] == pytest.approx(1.0e6 + 250000.0, rel=1e-12)             # recomputation is the cheaper by 1658 us
+    assert do and tp_new == 4 and t_best == pytest.approx(rem4 + 1.0e6 + 250000.0, rel=1e-12)
+    # a network twice as fast: migration (125 829.12 us) wins
+    _, _, _, _, totals = oc.decide(p, 1, [1, 4], groups, 4000, 3000, lengths, model, fixed, 50e9, 4, pf)
+    assert totals[1][2] == pytest.approx(1.0e6 + move / 2, rel=1e-12)
+    # recomputation so cheap it flips a decision that migration alone loses: 100 steps left
+    pf2 = oc.PrefillTable([(4, 4, 3000, 10.0)])
+    slow = oc.decide(p, 1, [1, 4], groups, 3100, 3000, lengths, model, {(1, 4): 0.0, (1, 1): 0.0}, 1e6, 4, None)
+    fast = oc.decide(p, 1, [1, 4], groups, 3100, 3000, lengths, model, {(1, 4): 0.0, (1, 1): 0.0}, 1e6, 4, pf2)
+    assert not slow[0] and fast[0] and fast[1] == 4 and fast[4][1][2] == pytest.approx(10.0)
+
+
+def test_prefill_table_ignores_unmeasured_rows_and_rejects_duplicates():
+    rows = [(4, 2, 1000, 10.0), (4, 2, 2000, 30.0), (4, 2, 4000, 110.0)]
+    marked = rows + [(4, 2, 3000, -1.0), (4, 2, 8000, -1.0), (4, 16, 1000, -1.0), (2, 2, 1000, float("nan"))]
+    a, b = oc.PrefillTable(rows), oc.PrefillTable(marked)
+    for L in (500, 1500, 3000, 3500, 9000):
+        assert a.query(4, 2, L) == b.query(4, 2, L)
+        assert a.query(4, 16, L) == b.query(4, 16, L)          # batch 16 had only an unmeasured row: no curve of its own
+    assert b.query(4, 2, 3000) == pytest.approx(70.0)           # through the measured neighbours, not through -1
+    assert b.query(2, 2, 1000) == math.inf                      # nothing measured for TP 2
+    with pytest.raises(ValueError):
+        oc.PrefillTable(rows + [(4, 2, 2000, 31.0)])
