@@ -69,8 +69,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int qua
             // stored rows (p0, p0+1) are natural (j0, j0 + D/2); (p0+2, p0+3) are (j0+1, j0+1 + D/2)
             const int j0 = p0 >> 1;
             const float4 cs = *reinterpret_cast<const float4 *>(a.rope_cs + ((int64_t)pos * half + j0) * 2);
-            const float r00 = v.x * cs.x - v.y * cs.y, r01 = v.x * cs.y + v.y * cs.x;
-            const float r10 = v.z * cs.z - v.w * cs.w, r11 = v.z * cs.w + v.w * cs.z;
+            // every product and sum rounded on its own (no fused multiply-add): the appended bytes are then a
+            // function of the fp32 projection output that a host can restate exactly
+            const float r00 = __fsub_rn(__fmul_rn(v.x, cs.x), __fmul_rn(v.y, cs.y)), r01 = __fadd_rn(__fmul_rn(v.x, cs.y), __fmul_rn(v.y, cs.x));
+            const float r10 = __fsub_rn(__fmul_rn(v.z, cs.z), __fmul_rn(v.w, cs.w)), r11 = __fadd_rn(__fmul_rn(v.z, cs.w), __fmul_rn(v.w, cs.z));
             if (head < a.hq) {
                 float *q = a.y + (int64_t)b * a.ldy + head * D;
                 *reinterpret_cast<float2 *>(q + j0) = make_float2(r00, r10);
