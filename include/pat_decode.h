@@ -268,6 +268,19 @@ int64_t pat_op_gemm_scratch_bytes(int32_t n, int32_t k, int32_t b);
 int pat_op_gemm_plan(int32_t n, int32_t k, int32_t b, int32_t plan[4]);
 int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b,
                 float *y, int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *scratch, void *hip_stream);
+/* pat_op_gemm for callers that cannot allocate device memory or hand over a work buffer: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * pat_op_gemm without `scratch`: the partial sums of a K split across workgroups go to an array that
+ * lives inside the library's code object, PAT_STATIC_SCRATCH_BYTES per GPU, held until the process ends.
+ * Returns PAT_ENOMEM, before anything is enqueued, when pat_op_gemm_scratch_bytes(n, k, b) exceeds
+ * that size (use pat_op_gemm with a buffer of your own then).  Calls no hipMalloc / hipFree and no
+ * allocating routine; the first call on a device looks the array's address up once.  All calls on one
+ * GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race; calls
+ * on one stream are ordered and safe.  Nothing needs clearing between calls: a call reads only the
+ * partial sums it wrote itself. */
+#define PAT_STATIC_SCRATCH_BYTES (32 << 20)
+int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b,
+                       float *y, int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *hip_stream);
 /* RMSNorm of x [b, h] with gains g [h] bf16 into packed split-bf16 activations. */
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo,
                         void *hip_stream);

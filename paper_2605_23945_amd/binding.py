@@ -82,7 +82,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_la
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
            "pat_kv_move_seconds", "pat_rms_length"]
 
@@ -130,6 +130,7 @@ def load_library() -> C.CDLL:
     lib.pat_op_pack_weight.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp]
     lib.pat_op_pack_act.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.pat_op_gemm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, C.c_int32, vp, vp]
+    lib.pat_op_gemm_static.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, C.c_int32, vp]
     lib.pat_op_gemm_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.pat_op_gemm_scratch_bytes.restype = C.c_int64
     lib.pat_op_gemm_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
@@ -365,6 +366,14 @@ def pat_op_gemm(w_packed, n, k, xhi, xlo, b, y=None, mode=0, y_hi=None, y_lo=Non
                          _ptr(y_hi), _ptr(y_lo), mode, _ptr(scratch), _stream())
     if rc:
         raise PatError(rc, "pat_op_gemm")
+
+
+def pat_op_gemm_static(w_packed, n, k, xhi, xlo, b, y=None, mode=0, y_hi=None, y_lo=None):
+    """pat_op_gemm with the library's own static scratch: no allocation on this path, torch's included."""
+    rc = load_library().pat_op_gemm_static(_ptr(w_packed), n, k, _ptr(xhi), _ptr(xlo), b, _ptr(y),
+                                           (y.stride(0) if y is not None else 0), _ptr(y_hi), _ptr(y_lo), mode, _stream())
+    if rc:
+        raise PatError(rc, "pat_op_gemm_static" + (": the K-slice partial sums exceed PAT_STATIC_SCRATCH_BYTES" if rc == PAT_ENOMEM else ""))
 
 
 def pat_op_rmsnorm_pack(x, g, eps):

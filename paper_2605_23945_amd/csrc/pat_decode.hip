@@ -11,6 +11,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -1003,6 +1004,53 @@ int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, con
     if (pat_op_gemm_scratch_bytes(n, k, b) > 0) {
         if (!scratch || ((uintptr_t)scratch & (kAlign - 1))) return PAT_EINVAL;
         g.part = (float *)scratch;
+    }
+    return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+// Scratch of pat_op_gemm_static: the K-slice partial sums live in this array instead of a caller's
+// buffer.  One copy per GPU, held until the process ends.  In host code the array's name is only a
+// handle: the device address comes from hipGetSymbolAddress, once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[PAT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *xhi, const void *xlo, int32_t b, float *y,
+                       int32_t ldy, void *y_hi, void *y_lo, int32_t mode, void *stream)
+{
+    if (!w_packed || !xhi || !xlo || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256 || mode < 0 || mode > 2) return PAT_EINVAL;
+    if (mode == kGemmSwiGLU) { if (!y_hi || !y_lo || n % 2 || (n / 2) % 32) return PAT_EINVAL; }
+    else if (!y || ldy < n) return PAT_EINVAL;
+    const int64_t need = pat_op_gemm_scratch_bytes(n, k, b);
+    if (need > (int64_t)PAT_STATIC_SCRATCH_BYTES) return PAT_ENOMEM;     // before any GPU call: nothing was enqueued
+    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr);
+    g.yhi = (uint4 *)y_hi; g.ylo = (uint4 *)y_lo; g.KS_out = mode == kGemmSwiGLU ? n / 2 / 32 : 0;
+    if (need > 0) {
+        void *p = nullptr;
+        if (static_scratch(&p) != hipSuccess) return PAT_EHIP;
+        g.part = (float *)p;          // every partial that is read was written by this call: nothing to clear
     }
     return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }

@@ -34,3 +34,13 @@ def test_host_only_calls_reject_bad_arguments_without_a_gpu():
     cfg = pat.pat_cfg()
     req = pat.pat_mem_req()
     assert lib.pat_decode_query(cfg, req) == pat.binding.PAT_EINVAL
+
+
+def test_static_scratch_entry_point_refuses_oversized_partial_sums_without_a_gpu():
+    """pat_op_gemm_static checks the size of the K-slice partial sums before any GPU call."""
+    lib = pat.load_library()
+    n, k, b = 22016, 4096, 256
+    assert lib.pat_op_gemm_scratch_bytes(n, k, b) > (32 << 20)
+    one = 0x1000                                                 # never dereferenced: the call fails first
+    assert lib.pat_op_gemm_static(one, n, k, one, one, b, one, n, None, None, 0, None) == pat.binding.PAT_ENOMEM
+    assert lib.pat_op_gemm_static(None, n, k, one, one, b, one, n, None, None, 0, None) == pat.binding.PAT_EINVAL
