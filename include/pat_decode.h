@@ -239,6 +239,12 @@ int pat_step_algo_bytes(pat_ctx *ctx, double *weight_bytes, double *kv_bytes);
 int pat_timing_enable(pat_ctx *ctx, int32_t on);
 int pat_timing_read(pat_ctx *ctx, int32_t klass, double *total_ms, int64_t *launches, int32_t reset);
 
+/* Diagnostics of the fused layer kernel (live batch <= 16): with trace_dev != NULL (device, 256 workgroups x 16 x 8
+ * bytes, kept alive by the caller until reset to NULL) every fused launch writes, per workgroup, the 100 MHz
+ * wall-clock stamps at its phase boundaries: start, then before and after each of the four device-wide barriers
+ * (merge | O | gate/up | down | next projection), then the end.  Each launch overwrites the last one's stamps. */
+int pat_timing_fused_trace(pat_ctx *ctx, void *trace_dev);
+
 int pat_decode_destroy(pat_ctx *ctx);
 const char *pat_last_error(const pat_ctx *ctx);   /* owned by ctx; "" if none */
 
@@ -284,6 +290,17 @@ int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *x
 /* RMSNorm of x [b, h] with gains g [h] bf16 into packed split-bf16 activations. */
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo,
                         void *hip_stream);
+/* The two operators with which a live batch of at most 16 rows enters a layer (the decode step folds every
+ * RMSNorm into the projection that consumes it):
+ *   pat_op_embed_stats: x[b, h] fp32 = rows tok[i] of a bf16 [vocab, h] table, stats[i] = sum of squares of row i
+ *     (tok device int32[b]; stats device float[16]);
+ *   pat_op_gemm_norm: y[b, n] = RMSNorm(x; g, eps) W^T with W [n, k] in streaming layout, x [16, k] fp32 (rows past
+ *     b are padding that is never used), g [k] bf16, and the rows' sums of squares given as n_parts partial sums
+ *     stats[part][16] that are added in a fixed order (n_parts = 1 after pat_op_embed_stats).  b <= 16.
+ *     PAT_ESTATE if the device cannot hold the kernel. */
+int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, int32_t b, float *x, float *stats, void *hip_stream);
+int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const float *x, const void *g, const float *stats,
+                     int32_t n_parts, float eps, int32_t b, float *y, int32_t ldy, void *hip_stream);
 /* (max, lowest index) per row of logits [b, n]; out_idx[b] = base + index. NaN counts as -inf. */
 int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val,
                   void *hip_stream);

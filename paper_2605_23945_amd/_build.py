@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpat_decode.so")
-SOURCES = ["gemm_stream.hip", "attention.hip", "step_misc.hip", "pat_decode.hip", "pat_switch.cpp"]
+SOURCES = ["gemm_stream.hip", "attention.hip", "layer_fused.hip", "step_misc.hip", "pat_decode.hip", "pat_switch.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-Wall"]          # host-only sources (.cpp)
@@ -31,7 +31,7 @@ def build_library(verbose: bool = False) -> str:
             print(err)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB],
                        capture_output=True, text=True)

@@ -80,9 +80,9 @@ class pat_switch_decision(C.Structure):
 
 EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_layer_from_full", "pat_load_final", "pat_decode_admit",
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
-           "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read",
+           "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read", "pat_timing_fused_trace",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_argmax",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_gemm_norm", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
            "pat_kv_move_seconds", "pat_rms_length"]
 
@@ -120,6 +120,7 @@ def load_library() -> C.CDLL:
     lib.pat_step_algo_bytes.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.pat_timing_enable.argtypes = [vp, C.c_int32]
     lib.pat_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]
+    lib.pat_timing_fused_trace.argtypes = [vp, vp]
     lib.pat_decode_destroy.argtypes = [vp]
     lib.pat_last_error.argtypes = [vp]
     lib.pat_last_error.restype = C.c_char_p
@@ -137,6 +138,8 @@ def load_library() -> C.CDLL:
     lib.pat_op_gemm_plan.restype = C.c_int
     lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
+    lib.pat_op_embed_stats.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp, vp]
+    lib.pat_op_gemm_norm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.c_int32, C.c_float, C.c_int32, vp, C.c_int32, vp]
     dp = C.POINTER(C.c_double)
     lib.pat_predictor_fit.argtypes = [C.POINTER(pat_grid_row), C.c_int32, C.POINTER(vp)]
     lib.pat_predictor_destroy.argtypes = [vp]
@@ -324,6 +327,10 @@ class Decoder:
     def pat_timing_enable(self, on: bool):
         self._chk(self.lib.pat_timing_enable(self.ctx, int(on)))
 
+    def pat_timing_fused_trace(self, trace):
+        """trace: int64 device tensor of 256 x 16 words (or None to switch the stamps off)."""
+        self._chk(self.lib.pat_timing_fused_trace(self.ctx, _ptr(trace)))
+
     def pat_timing_read(self, klass, reset=True):
         ms, n = C.c_double(), C.c_int64()
         self._chk(self.lib.pat_timing_read(self.ctx, klass, C.byref(ms), C.byref(n), int(reset)))
@@ -386,6 +393,30 @@ def pat_op_rmsnorm_pack(x, g, eps):
     if rc:
         raise PatError(rc, "pat_op_rmsnorm_pack")
     return hi, lo
+
+
+def pat_op_embed_stats(table, tok):
+    """table bf16 [vocab, h], tok int32 [b <= 16] (device) -> (x fp32 [16, h] with rows >= b unset, stats fp32 [16])."""
+    import torch
+    b, h = tok.shape[0], table.shape[1]
+    x = torch.zeros(16, h, dtype=torch.float32, device=table.device)
+    stats = torch.zeros(16, dtype=torch.float32, device=table.device)
+    rc = load_library().pat_op_embed_stats(_ptr(table), h, _ptr(tok), b, _ptr(x), _ptr(stats), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_embed_stats")
+    return x, stats
+
+
+def pat_op_gemm_norm(w_packed, n, k, x, g, stats, eps, b):
+    """y [b, n] = RMSNorm(x[:b]; g, eps) W^T; x fp32 [16, k], stats fp32 [n_parts, 16] partial sums of squares."""
+    import torch
+    assert x.shape == (16, k) and x.is_contiguous() and stats.is_contiguous() and stats.numel() % 16 == 0
+    y = torch.empty(b, n, dtype=torch.float32, device=x.device)
+    rc = load_library().pat_op_gemm_norm(_ptr(w_packed), n, k, _ptr(x), _ptr(g), _ptr(stats), stats.numel() // 16, eps, b,
+                                         _ptr(y), n, _stream())
+    if rc:
+        raise PatError(rc, "pat_op_gemm_norm")
+    return y
 
 
 def pat_op_argmax(logits, base=0):

@@ -21,105 +21,12 @@
 // depend on timing.
 #include <algorithm>
 #include <cstdlib>
-#include "pat_dev.h"
-#include "pat_kernels.h"
+#include <mutex>
+#include "gemm_dev.h"
 
 namespace pat {
 
 namespace {
-
-
-__device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                   0, 0, 0);
-}
-
-// Native vector flavour of a 16-byte fragment.  Values that are loaded in one loop iteration and
-// used in a later one are held in this type: assignments of the runtime's uint4 class can be
-// lowered to memcpy between address spaces, which pins the variable in scratch memory.
-__device__ __forceinline__ u32x4_t ld16(const uint4 *p) { return *reinterpret_cast<const u32x4_t *>(p); }
-__device__ __forceinline__ void st16(uint4 *p, u32x4_t v) { *reinterpret_cast<u32x4_t *>(p) = v; }
-__device__ __forceinline__ floatx4_t mfma16(u32x4_t a, uint4 b, floatx4_t c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                   0, 0, 0);
-}
-
-__device__ __forceinline__ floatx4_t mfma16(u32x4_t a, u32x4_t b, floatx4_t c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                   0, 0, 0);
-}
-
-__device__ __forceinline__ float silu(float z) { return z / (1.0f + expf(-z)); }
-
-// Epilogue for a float4 = 4 consecutive output features (rows 16 rt + 4 quad ..) of batch row b.
-template <int MODE>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int quad, int b, float4 v)
-{
-    if (b >= a.B) return;
-    if (MODE == kGemmQKV) {
-        const int n = rt * 16 + quad * 4;                 // stored row: 4 | n, so a quad never straddles heads
-        if (n >= a.n_valid) return;
-        const int D = a.kv.d, half = D >> 1, P = a.kv.P;
-        const int head = n / D, p0 = n - head * D;
-        const int pos = a.kv_len[b];
-        if (head < a.hq + a.kv.hkv) {
-            // stored rows (p0, p0+1) are natural (j0, j0 + D/2); (p0+2, p0+3) are (j0+1, j0+1 + D/2)
-            const int j0 = p0 >> 1;
-            const float4 cs = *reinterpret_cast<const float4 *>(a.rope_cs + ((int64_t)pos * half + j0) * 2);
-            // every product and sum rounded on its own (no fused multiply-add): the appended bytes are then a
-            // function of the fp32 projection output that a host can restate exactly
-            const float r00 = __fsub_rn(__fmul_rn(v.x, cs.x), __fmul_rn(v.y, cs.y)), r01 = __fadd_rn(__fmul_rn(v.x, cs.y), __fmul_rn(v.y, cs.x));
-            const float r10 = __fsub_rn(__fmul_rn(v.z, cs.z), __fmul_rn(v.w, cs.w)), r11 = __fadd_rn(__fmul_rn(v.z, cs.w), __fmul_rn(v.w, cs.z));
-            if (head < a.hq) {
-                float *q = a.y + (int64_t)b * a.ldy + head * D;
-                *reinterpret_cast<float2 *>(q + j0) = make_float2(r00, r10);
-                *reinterpret_cast<float2 *>(q + j0 + half) = make_float2(r01, r11);
-            } else {
-                const int page = a.page_table[(int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages + pos / P];
-                uint16_t *kd = a.kv.pool + a.kv.base(a.layer, 0) + page * a.kv.page_elems() +
-                               ((int64_t)(head - a.hq) * P + (pos % P)) * D;
-                *reinterpret_cast<uint32_t *>(kd + j0) = (uint32_t)f32_to_bf16(r00) | ((uint32_t)f32_to_bf16(r10) << 16);
-                *reinterpret_cast<uint32_t *>(kd + j0 + half) = (uint32_t)f32_to_bf16(r01) | ((uint32_t)f32_to_bf16(r11) << 16);
-            }
-        } else {
-            const int page = a.page_table[(int64_t)(a.row_slot ? a.row_slot[b] : b) * a.max_pages + pos / P];
-            uint16_t *vd = a.kv.pool + a.kv.base(a.layer, 1) + page * a.kv.page_elems() +
-                           ((int64_t)(head - a.hq - a.kv.hkv) * P + (pos % P)) * D + p0;
-            *reinterpret_cast<uint2 *>(vd) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
-                                                        (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
-        }
-    } else if (MODE == kGemmSwiGLU) {
-        // rows alternate gate, up: (g f0, u f0, g f0+1, u f0+1)
-        const int f0 = rt * 8 + quad * 2;
-        if (2 * f0 < a.n_valid) {
-            uint16_t h0, l0, h1, l1;
-            split_bf16(silu(v.x) * v.y, h0, l0);
-            split_bf16(silu(v.z) * v.w, h1, l1);
-            const int64_t off = packed_elem_offset(b, f0, a.KS_out);   // f0 even: 4-byte aligned pair
-            reinterpret_cast<uint32_t *>(a.yhi)[off >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            reinterpret_cast<uint32_t *>(a.ylo)[off >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-        }
-    } else {
-        const int n = rt * 16 + quad * 4;
-        float *yp = a.y + (int64_t)b * a.ldy + n;
-        if (n + 3 < a.n_valid) {
-            float4 o = v;
-            if (MODE == kGemmAccum) {
-                const float4 c = *reinterpret_cast<const float4 *>(yp);
-                o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
-            }
-            *reinterpret_cast<float4 *>(yp) = o;
-        } else {
-            const float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (n + i < a.n_valid) { if (MODE == kGemmAccum) yp[i] += vv[i]; else yp[i] = vv[i]; }
-        }
-    }
-}
 
 // K-slice partial of (row tile rt, quad, batch row b): part[kb][b][n_tiles*16]
 __device__ __forceinline__ void store_partial(const GemmArgs &a, int kb, int rt, int quad, int b, float4 v)
@@ -522,20 +429,23 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *x, const
              *reinterpret_cast<const uint4 *>(g + k0));
 }
 
+// the kernels' dynamic LDS exceeds the default limit: raised per device by gemm_prepare_device()
+template <int NB, int UK, int TB, int kXsWaves>
+hipError_t xs_set_lds_limit()
+{
+    constexpr size_t lds = (size_t)TB * kXsWaves * NB * 64 * sizeof(float4);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    return e;
+}
+
 template <int NB, int UK, int TB, int kXsWaves>
 hipError_t launch_xs(const GemmArgs &a, int mode, hipStream_t s)
 {
     const unsigned grid = (unsigned)a.Rg;
     constexpr size_t lds = (size_t)TB * kXsWaves * NB * 64 * sizeof(float4);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     switch (mode) {
     case kGemmStore: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmStore><<<grid, kXsWaves * 64, lds, s>>>(a); break;
     case kGemmAccum: gemm_xs_kernel<NB, UK, TB, kXsWaves, kGemmAccum><<<grid, kXsWaves * 64, lds, s>>>(a); break;
@@ -560,6 +470,22 @@ hipError_t launch_xb(const GemmArgs &a, int mode, hipStream_t s)
 }
 
 }  // namespace
+
+// Once per device and process (the attribute belongs to the device's copy of the kernel); a bit per device id.
+hipError_t gemm_prepare_device()
+{
+    static std::mutex mu;
+    static uint64_t done = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev >= 0 && dev < 64 && (done >> dev & 1)) return hipSuccess;
+    e = xs_set_lds_limit<1, 8, 8, 16>();
+    if (e == hipSuccess) e = xs_set_lds_limit<2, 8, 8, 8>();
+    if (e == hipSuccess && dev >= 0 && dev < 64) done |= 1ull << dev;
+    return e;
+}
 
 static int g_target_wgs = 256;   // one resident workgroup per compute unit
 void gemm_set_compute_units(int n) { if (n > 0) g_target_wgs = n; }
@@ -611,8 +537,9 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     GemmArgs a = a0;
     const GemmPlan p = gemm_plan(a.n_tiles, a.KS, a.B);
     a.Kb = p.Kb; a.Rg = p.Rg;
-    if (a.Kb > 1 && a.part == nullptr) return hipErrorInvalidValue;
+    if (a.Kb > 1 && (a.part == nullptr || (int64_t)a.Kb * a.B * a.n_tiles * 64 > a.part_bytes)) return hipErrorInvalidValue;
     // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
+    if (a.B <= 32) { const hipError_t e = gemm_prepare_device(); if (e != hipSuccess) return e; }
     if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
     if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
     const hipError_t e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s)

@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -33,6 +34,10 @@ struct WorkLayout {   // byte offsets inside the work arena
     int64_t seq_id, tok, kv_len, gen, target, fin, page_table, page_table_tmp, free_stack, scalars, chunk_start, chunk_meta, tmp;
     int64_t total;
     int64_t max_chunks;
+    int64_t gemm_part_bytes;
+    // fused layer kernel (live batch <= 16): three rotating residual buffers, packed o and SwiGLU outputs,
+    // sums of squares, barrier words
+    int64_t xr[3], o_hi, o_lo, act_hi, act_lo, stats_e, stats1, stats2, sync;
 };
 
 struct WeightLayout {  // byte offsets inside the weights arena
@@ -66,6 +71,10 @@ struct pat_ctx {
     std::vector<int32_t> seq_id, kv_len, gen, target, fin;
     int64_t n_free = 0;
     int64_t step_index = 0;
+    // fused layer kernel (live batch <= 16)
+    bool fused_ok = false;          // the kernel fits one workgroup per compute unit on this device
+    unsigned sync_gen = 1;          // number of the next device-wide barrier since the words were zeroed
+    unsigned long long *fused_trace = nullptr;   // diagnostics: phase stamps of the fused launches (caller's device buffer)
     // pinned staging
     int32_t *pinned = nullptr;      // 6 * max_batch ints + report
     int32_t *pf_stage = nullptr;    // pinned: block records of one prefill pass (kPfRecords x 8 ints)
@@ -158,9 +167,16 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
                 const int kb = gemm_plan(mt[0], mt[1], b).Kb;
                 if (kb > 1) need = std::max(need, (int64_t)kb * b * mt[0] * 16 * 4);
             }
-        w->gemm_part = take(std::max<int64_t>(need, 256));
+        w->gemm_part_bytes = std::max<int64_t>(need, 256);
+        w->gemm_part = take(w->gemm_part_bytes);
 
     }
+    for (int i = 0; i < 3; ++i) w->xr[i] = take((int64_t)kFusedMaxBatch * s.H * 4);
+    w->o_hi = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d)); w->o_lo = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d));
+    w->act_hi = take(packed_x_bytes(kFusedMaxBatch, s.F)); w->act_lo = take(packed_x_bytes(kFusedMaxBatch, s.F));
+    w->stats_e = take(16 * 4);
+    w->stats1 = take((int64_t)cdiv(s.H, 16) * 16 * 4); w->stats2 = take((int64_t)cdiv(s.H, 16) * 16 * 4);
+    w->sync = take((int64_t)kFusedSyncWords * 4);
     w->max_chunks = c->kv_token_budget / kMinChunk + 2 * (int64_t)MB;
     w->chunk_meta = take(w->max_chunks * 32);
     w->part_acc = take(w->max_chunks * s.hq * s.d * 4);
@@ -233,11 +249,12 @@ int flush_timing(pat_ctx *c)
     return PAT_OK;
 }
 
-GemmArgs gemm_args(const void *w, int n, int k, const uint4 *xhi, const uint4 *xlo, int B, float *y, int ldy, float *part)
+GemmArgs gemm_args(const void *w, int n, int k, const uint4 *xhi, const uint4 *xlo, int B, float *y, int ldy, float *part,
+                   int64_t part_bytes)
 {
     GemmArgs g{};
     g.w = (const uint4 *)w; g.n_tiles = cdiv(n, 16); g.KS = k / 32; g.xhi = xhi; g.xlo = xlo; g.B = B;
-    g.y = y; g.ldy = ldy; g.n_valid = n; g.part = part; g.Kb = 1; g.Rg = 1;
+    g.y = y; g.ldy = ldy; g.n_valid = n; g.part = part; g.part_bytes = part ? part_bytes : 0; g.Kb = 1; g.Rg = 1;
     return g;
 }
 
@@ -360,6 +377,18 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
     }
     e = launch_pool_init(c->st, s.n_pages, c->stream);
     if (e != hipSuccess) return die("pool init", e);
+    e = gemm_prepare_device();
+    if (e != hipSuccess) return die("projection kernel set-up", e);
+    {
+        bool usable = false;
+        e = fused_prepare(c->n_cu, &usable);
+        if (e != hipSuccess) return die("fused layer kernel set-up", e);
+        const char *on = getenv("PAT_ENABLE_FUSED");         // off unless asked for while it is slower than the unfused path
+        c->fused_ok = usable && on && on[0] == '1';
+        e = launch_sync_reset(at<unsigned>(W, w.sync), kFusedSyncWords, c->stream);
+        if (e != hipSuccess) return die("barrier words", e);
+        c->sync_gen = 1;
+    }
     *out = c;
     return PAT_OK;
 }
@@ -585,7 +614,7 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
         char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
-            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart);
+            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart, w.gemm_part_bytes);
             if (!c->cfg.qk_norm) {
                 g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = pos; g.row_slot = row_slot;
                 g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
@@ -608,19 +637,107 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
             PAT_HIP(c, launch_attn_merge(aa, st));
         }
         {
-            GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart);
+            GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart, w.gemm_part_bytes);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
         { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
-            GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart);
+            GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart, w.gemm_part_bytes);
             g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
         }
         {
-            GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart);
+            GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart, w.gemm_part_bytes);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
+    }
+    return PAT_OK;
+}
+
+// The decode step of a live batch of at most 16 rows: per layer the attention partials and ONE fused launch
+// (merge, O, gate/up, down, next layer's QKV or the vocabulary head; see layer_fused.hip).  Leaves the logits
+// in `logits`.
+static int run_layers_fused(pat_ctx *c, int B, int C, int64_t n_chunks, float *logits)
+{
+    const Shard &s = c->sh;
+    void *W = c->bufs.work;
+    const WorkLayout &w = c->wl;
+    hipStream_t st = c->stream;
+    char *Wb = at<char>(c->bufs.weights, 0);
+    float *qkv = at<float>(W, w.qkv);
+    float *X[3] = {at<float>(W, w.xr[0]), at<float>(W, w.xr[1]), at<float>(W, w.xr[2])};
+    const int n_parts = cdiv(s.H, 16);
+
+    AttnArgs aa{};
+    aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = c->st.kv_len; aa.row_slot = nullptr;
+    aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_meta = c->st.chunk_meta; aa.chunk_tokens = C;
+    aa.part_acc = at<float>(W, w.part_acc); aa.part_ml = at<float>(W, w.part_ml);
+    aa.ohi = at<uint4>(W, w.o_hi); aa.olo = at<uint4>(W, w.o_lo);
+    aa.n_items = (int)(n_chunks * s.hkv);
+
+    FusedArgs fa{};
+    fa.B = B; fa.H = s.H; fa.merge = aa;
+    fa.stats1 = at<float>(W, w.stats1); fa.stats2 = at<float>(W, w.stats2);
+    fa.sync = at<unsigned>(W, w.sync); fa.max_spin = 400000u; fa.err = c->st.scalars + 7; fa.trace = c->fused_trace;
+
+    // the projection of layer `l` (or the head for l == NL) that closes a launch: RMSNorm of `x` with that layer's gains
+    auto set_next = [&](int l, const float *x, const float *stats, int parts) {
+        if (l < s.NL) {
+            char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
+            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, nullptr, nullptr, B, qkv, s.qkv_rows, nullptr, 0);
+            if (!c->cfg.qk_norm) {
+                g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len; g.row_slot = nullptr;
+                g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
+                fa.next_mode = kGemmQKV;
+            } else fa.next_mode = kGemmStore;
+            fa.next = g;
+            fa.n_next = NormIn{x, (const uint16_t *)(L + c->wt.g1), stats, parts, s.H, c->cfg.rms_eps};
+        } else {
+            fa.next = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, nullptr, nullptr, B, logits, s.Vs, nullptr, 0);
+            fa.next_mode = kGemmStore;
+            fa.n_next = NormIn{x, (const uint16_t *)(Wb + c->wt.gf), stats, parts, s.H, c->cfg.rms_eps};
+        }
+    };
+    // model family with per-head q/k normalisation: the plain projection is followed by the kernel that normalises, rotates and appends
+    auto qk_norm_tail = [&](int l) -> int {
+        if (!c->cfg.qk_norm || l >= s.NL) return PAT_OK;
+        char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
+        TimeScope t(c, 2);
+        PAT_HIP(c, launch_qknorm_rope_append(qkv, s.qkv_rows, s.hq, c->kv, l, c->st.kv_len, nullptr, c->st.page_table, s.max_pages,
+                                             at<float>(W, w.rope), (const uint16_t *)(L + c->wt.gq), (const uint16_t *)(L + c->wt.gk),
+                                             c->cfg.rms_eps, B, st));
+        return PAT_OK;
+    };
+
+    {   // embedding + its sums of squares, then the first layer's QKV alone
+        TimeScope t(c, 2);
+        PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, X[0], at<float>(W, w.stats_e), st));
+    }
+    fa.p_begin = 4;
+    set_next(0, X[0], at<float>(W, w.stats_e), 1);
+    fa.gen0 = c->sync_gen;
+    { TimeScope t(c, 0); PAT_HIP(c, launch_layer_fused(fa, c->n_cu, st)); }
+    if (int rc = qk_norm_tail(0)) return rc;
+
+    for (int l = 0; l < s.NL; ++l) {
+        char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
+        aa.layer = l;
+        { TimeScope t(c, 1); PAT_HIP(c, launch_attn_partial(aa, st)); }
+        const float *x_in = X[(2 * l) % 3];
+        float *x1 = X[(2 * l + 1) % 3], *x2 = X[(2 * l + 2) % 3];
+        fa.p_begin = 0;
+        fa.merge = aa;
+        fa.x_in = x_in; fa.x1 = x1; fa.x2 = x2;
+        fa.o = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, aa.ohi, aa.olo, B, nullptr, s.H, nullptr, 0);
+        fa.gu = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, nullptr, nullptr, B, nullptr, 0, nullptr, 0);
+        fa.gu.yhi = at<uint4>(W, w.act_hi); fa.gu.ylo = at<uint4>(W, w.act_lo); fa.gu.KS_out = s.F / 32;
+        fa.n_gu = NormIn{x1, (const uint16_t *)(L + c->wt.g2), fa.stats1, n_parts, s.H, c->cfg.rms_eps};
+        fa.down = gemm_args(L + c->wt.wd, s.H, s.F, fa.gu.yhi, fa.gu.ylo, B, nullptr, s.H, nullptr, 0);
+        set_next(l + 1, x2, fa.stats2, n_parts);
+        fa.gen0 = c->sync_gen;
+        c->sync_gen += 4;                                   // merge | O | gate/up | down | next: four barriers
+        { TimeScope t(c, 0); PAT_HIP(c, launch_layer_fused(fa, c->n_cu, st)); }
+        if (int rc = qk_norm_tail(l + 1)) return rc;
     }
     return PAT_OK;
 }
@@ -656,13 +773,16 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     float *gpart = at<float>(W, w.gemm_part);
 
     { TimeScope t(c, 2); PAT_HIP(c, launch_plan_step(c->st, B, C, st)); }
-    { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
-
-    if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr, 0)) return rc;
-    { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
-    {
-        GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart);
-        TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
+    if (B <= kFusedMaxBatch && c->fused_ok) {
+        if (int rc = run_layers_fused(c, B, C, n_chunks, logits)) return rc;
+    } else {
+        { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
+        if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr, 0)) return rc;
+        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        {
+            GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart, w.gemm_part_bytes);
+            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
+        }
     }
     { TimeScope t(c, 2); PAT_HIP(c, launch_argmax(logits, B, s.Vs, s.vocab0, next_tok, at<float>(W, w.best_val), st)); }
     { TimeScope t(c, 2); PAT_HIP(c, launch_finish(c->st, next_tok, B, c->cfg.eos_token, at<char>(W, w.report), st)); }
@@ -816,6 +936,8 @@ int pat_decode_reset(pat_ctx *c)
 {
     if (!c) return PAT_EINVAL;
     PAT_HIP(c, launch_pool_init(c->st, c->sh.n_pages, c->stream));
+    PAT_HIP(c, launch_sync_reset(at<unsigned>(c->bufs.work, c->wl.sync), kFusedSyncWords, c->stream));
+    c->sync_gen = 1;
     c->live = 0; c->n_free = c->sh.n_pages;
     std::fill(c->fin.begin(), c->fin.end(), 0);
     return PAT_OK;
@@ -936,6 +1058,13 @@ int pat_timing_enable(pat_ctx *c, int32_t on)
     return rc;
 }
 
+int pat_timing_fused_trace(pat_ctx *c, void *trace_dev)
+{
+    if (!c) return PAT_EINVAL;
+    c->fused_trace = (unsigned long long *)trace_dev;
+    return PAT_OK;
+}
+
 int pat_timing_read(pat_ctx *c, int32_t klass, double *total_ms, int64_t *launches, int32_t reset)
 {
     if (!c || klass < 0 || klass > 2) return PAT_EINVAL;
@@ -999,11 +1128,11 @@ int pat_op_gemm(const void *w_packed, int32_t n, int32_t k, const void *xhi, con
     if (!w_packed || !xhi || !xlo || n <= 0 || k <= 0 || k % 32 || b <= 0 || b > 256 || mode < 0 || mode > 2) return PAT_EINVAL;
     if (mode == kGemmSwiGLU) { if (!y_hi || !y_lo || n % 2 || (n / 2) % 32) return PAT_EINVAL; }
     else if (!y || ldy < n) return PAT_EINVAL;
-    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr);
+    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr, 0);
     g.yhi = (uint4 *)y_hi; g.ylo = (uint4 *)y_lo; g.KS_out = mode == kGemmSwiGLU ? n / 2 / 32 : 0;
     if (pat_op_gemm_scratch_bytes(n, k, b) > 0) {
         if (!scratch || ((uintptr_t)scratch & (kAlign - 1))) return PAT_EINVAL;
-        g.part = (float *)scratch;
+        g.part = (float *)scratch; g.part_bytes = pat_op_gemm_scratch_bytes(n, k, b);
     }
     return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
@@ -1045,14 +1174,38 @@ int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *x
     else if (!y || ldy < n) return PAT_EINVAL;
     const int64_t need = pat_op_gemm_scratch_bytes(n, k, b);
     if (need > (int64_t)PAT_STATIC_SCRATCH_BYTES) return PAT_ENOMEM;     // before any GPU call: nothing was enqueued
-    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr);
+    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xhi, (const uint4 *)xlo, b, y, ldy, nullptr, 0);
     g.yhi = (uint4 *)y_hi; g.ylo = (uint4 *)y_lo; g.KS_out = mode == kGemmSwiGLU ? n / 2 / 32 : 0;
     if (need > 0) {
         void *p = nullptr;
         if (static_scratch(&p) != hipSuccess) return PAT_EHIP;
-        g.part = (float *)p;          // every partial that is read was written by this call: nothing to clear
+        g.part = (float *)p; g.part_bytes = PAT_STATIC_SCRATCH_BYTES;   // every partial that is read was written by this call: nothing to clear
     }
     return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, int32_t b, float *x, float *stats, void *stream)
+{
+    if (!table || !tok || !x || !stats || h <= 0 || h % 32 || b <= 0 || b > kFusedMaxBatch) return PAT_EINVAL;
+    return launch_embed_stats((const uint16_t *)table, h, tok, b, x, stats, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const float *x, const void *g, const float *stats, int32_t n_parts,
+                     float eps, int32_t b, float *y, int32_t ldy, void *stream)
+{
+    if (!w_packed || !x || !g || !stats || !y || n <= 0 || k <= 0 || k % 32 || n_parts < 1 || b <= 0 || b > kFusedMaxBatch || ldy < n)
+        return PAT_EINVAL;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        return PAT_EHIP;
+    bool usable = false;
+    if (fused_prepare(n_cu, &usable) != hipSuccess) return PAT_EHIP;
+    if (!usable) return PAT_ESTATE;
+    FusedArgs fa{};
+    fa.B = b; fa.H = k; fa.p_begin = 4; fa.next_mode = kGemmStore;
+    fa.next = gemm_args(w_packed, n, k, nullptr, nullptr, b, y, ldy, nullptr, 0);
+    fa.n_next = NormIn{x, (const uint16_t *)g, stats, n_parts, k, eps};
+    return launch_layer_fused(fa, n_cu, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo, void *stream)

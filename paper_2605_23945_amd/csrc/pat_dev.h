@@ -46,6 +46,29 @@ __device__ __host__ __forceinline__ int64_t packed_elem_offset(int row, int k, i
     return ((((int64_t)tile * KS + ks) * 64 + g * 16 + r) << 3) + j;
 }
 
+// Agent-scope (write-through) stores and loads: data that another workgroup of the SAME launch reads after a
+// device-wide barrier is written with these, so that no cache-wide write-back is needed; the reader uses
+// plain loads provided the address was not read earlier in the launch (no stale line can exist then).
+__device__ __forceinline__ void store4_agent(void *p, uint32_t v)
+{
+    __hip_atomic_store(reinterpret_cast<uint32_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store8_agent(void *p, uint64_t v)
+{
+    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store16_agent(void *p, uint4 v)
+{
+    store8_agent(p, (uint64_t)v.x | ((uint64_t)v.y << 32));
+    store8_agent(reinterpret_cast<char *>(p) + 8, (uint64_t)v.z | ((uint64_t)v.w << 32));
+}
+__device__ __forceinline__ void storef4_agent(float *p, float4 v)
+{
+    store8_agent(p, (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32));
+    store8_agent(p + 2, (uint64_t)__float_as_uint(v.z) | ((uint64_t)__float_as_uint(v.w) << 32));
+}
+__device__ __forceinline__ void storef_agent(float *p, float v) { store4_agent(p, __float_as_uint(v)); }
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

@@ -34,6 +34,7 @@ struct GemmArgs {
     const int32_t *row_slot;   // slot (page-table row) of batch row b, or NULL: slot b
     const float *rope_cs;      // [pos][d/2][cos, sin]
     float *part;               // scratch for K-slice partials [Kb][B][n_tiles * 16], or NULL
+    int64_t part_bytes;        // its size: a plan that needs more is refused
     int Kb, Rg;                // set by launch_gemm from gemm_plan
 };
 // How a [16 n_tiles, 32 KS] projection at live batch B is cut: K slices across workgroups and row groups.
@@ -51,6 +52,8 @@ hipError_t launch_pack_act(const float *x, int b, int k, uint4 *hi, uint4 *lo, h
 hipError_t launch_rmsnorm_pack(const float *x, const uint16_t *g, int b, int h, float eps, uint4 *hi, uint4 *lo,
                                hipStream_t s);
 hipError_t launch_gemm(const GemmArgs &a, int mode, hipStream_t s);
+// sets the dynamic-LDS limit of the small-batch kernels on the current device (once per context)
+hipError_t gemm_prepare_device();
 
 // ---- attention over the paged cache (attention.hip) ----------------------------
 
@@ -75,6 +78,39 @@ struct AttnArgs {
 hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s);
+
+// ---- fused layer kernel for live batches <= 16 (layer_fused.hip) ------------------
+// fp32 rows whose RMSNorm is folded into a projection: scale 1 / sqrt(sum(x^2) / H + eps) from the per-part
+// sums of squares stats[part][16] (fixed summation order), times the gains g.
+struct NormIn {
+    const float *x;            // [16, H] (rows past the live batch are padding)
+    const uint16_t *g;         // [H] bf16
+    const float *stats;        // [n_parts][16]
+    int n_parts, H;
+    float eps;
+};
+struct FusedArgs {
+    int B, H;
+    int p_begin;               // first phase to run: 0 merge, 1 O, 2 gate/up, 3 down, 4 next projection only
+    int next_mode;             // kGemmQKV (next layer's QKV with rotary + append), kGemmStore (plain projection / head)
+    AttnArgs merge;            // P0: chunk partials -> packed o (merge.ohi / merge.olo)
+    GemmArgs o, gu, down, next;
+    NormIn n_gu, n_next;
+    const float *x_in;         // residual before the O projection
+    float *x1, *x2;            // residual after O / after down: each written in one phase only
+    float *stats1, *stats2;    // per-tile sums of squares of x1 / x2: [H / 16][16]
+    unsigned *sync;            // barrier words (see grid_sync), zeroed by launch_sync_reset
+    unsigned gen0;             // number of the launch's first barrier since the reset (host-counted)
+    unsigned max_spin;
+    int32_t *err;              // device error word (bit 2: a barrier wait gave up)
+    unsigned long long *trace; // NULL, or [n_wg][16] device words: wall-clock stamps of every workgroup at the phase boundaries
+};
+constexpr int kFusedSyncWords = 2048;      // 8 KiB
+constexpr int kFusedMaxBatch = 16;
+hipError_t fused_prepare(int n_cu, bool *usable);
+hipError_t launch_layer_fused(const FusedArgs &fa, int n_wg, hipStream_t s);
+hipError_t launch_embed_stats(const uint16_t *table, int H, const int32_t *tok, int B, float *x, float *stats, hipStream_t s);
+hipError_t launch_sync_reset(unsigned *w, int n_words, hipStream_t s);
 
 // ---- small kernels (step_misc.hip) ----------------------------------------------
 struct StateArrays {           // device int32 arrays of max_batch entries

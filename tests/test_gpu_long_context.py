@@ -89,12 +89,12 @@ def test_kv_append_bytes_are_the_rounding_of_the_projection_output(orc, hq, hkv,
     dec = make_decoder(shard, n, 1100, int(lens.sum()) + 64 * n + 256)
     pat.admit_synthetic(dec, shard, req, DEV)
     dec.pat_decode_step(True)
-    # the path's own fp32 k, v: embedding rows -> RMSNorm -> plain projection with the same operators
+    # the path's own fp32 k, v: the same two operators the step runs (embedding rows with their sums of squares,
+    # then the projection with the RMSNorm folded in), without the rotary / append epilogue
     w = pi.layer_weights(shard, 0, device=DEV)
-    x = pi.embedding_rows(shard, req["token"], device=DEV).float()
-    hi, lo = pat.pat_op_rmsnorm_pack(x, w["g1"], m.rms_eps)
-    y = torch.empty(n, shard.qkv_rows, device=DEV)
-    pat.pat_op_gemm(pat.pat_op_pack_weight(w["wqkv"]), shard.qkv_rows, H, hi, lo, n, y, mode=0)
+    table = pi.embedding_table(shard, device=DEV)
+    x, stats = pat.pat_op_embed_stats(table, torch.as_tensor(req["token"], dtype=torch.int32, device=DEV))
+    y = pat.pat_op_gemm_norm(pat.pat_op_pack_weight(w["wqkv"]), shard.qkv_rows, H, x, w["g1"], stats, m.rms_eps, n)
     y = y.cpu().numpy()
     half = d // 2
     inv = np.power(np.float64(m.rope_base), -2.0 * np.arange(half) / d)

@@ -135,3 +135,36 @@ def test_argmax_bit_exact(pat, orc):
         x = torch.randn(3, n, generator=g)
         idx, _ = pat.pat_op_argmax(x.to(DEV))
         assert idx.cpu().tolist() == [orc.argmax_f32(r.numpy()) for r in x]
+
+
+@pytest.mark.parametrize("n,k,b", [(256, 1024, 1), (1040, 4096, 16), (512, 5120, 7), (96, 8192, 3), (2048, 256, 16), (4096, 4096, 2),
+                                   (8000, 4096, 5)])
+def test_gemm_with_folded_rmsnorm_vs_oracle(pat, orc, n, k, b):
+    """The projection of the small-batch step: RMSNorm of fp32 rows folded into the operand load, the rows' sums of
+    squares supplied as per-16-column partial sums (what the producing projection writes).  Rows past the live
+    batch are padding and must not leak into any result (they are filled with NaN here)."""
+    w, x = _w(n, k, 7 + n + k), _x(b, k, 3 * n + b) * 3.0
+    g = pi.normal_bf16(pi.stream_key(1, 3), torch.arange(k, dtype=torch.int64), 0.02, 1.0)
+    x16 = torch.full((16, k), float("nan"))
+    x16[:b] = x
+    stats = (x16.view(16, k // 16, 16) ** 2).sum(-1).T.contiguous()           # [k / 16, 16]
+    wp = pat.pat_op_pack_weight(w.to(DEV))
+    y = pat.pat_op_gemm_norm(wp, n, k, x16.to(DEV), g.to(DEV), stats.to(DEV), 1e-6, b).cpu().double().numpy()
+    assert np.all(np.isfinite(y))
+    for r in sorted(set([0, b - 1, b // 2])):
+        ref = orc.matvec(bits(w), orc.rmsnorm(x[r].double().numpy(), bits(g), 1e-6))
+        scale = float(np.sqrt(np.mean(ref * ref)))
+        assert np.max(np.abs(y[r] - ref)) <= 1e-4 * scale
+    # one part per row (as after the embedding) gives the same 1/rms up to the summation order
+    y1 = pat.pat_op_gemm_norm(wp, n, k, x16.to(DEV), g.to(DEV), torch.nan_to_num((x16 ** 2).sum(-1), nan=0.0).to(DEV), 1e-6, b)
+    assert np.max(np.abs(y1.cpu().double().numpy() - y)) <= 1e-5 * float(np.sqrt(np.mean(y * y)))
+
+
+def test_embed_stats_rows_and_sums(pat):
+    s = pi.CONFIGS["tiny_tp1"]["shard"]
+    table = pi.embedding_table(s, device=DEV)
+    tok = torch.tensor([5, 0, 1023, 77, 5], dtype=torch.int32, device=DEV)
+    x, stats = pat.pat_op_embed_stats(table, tok)
+    ref = table[tok.long()].float()
+    assert torch.equal(x[:5], ref)
+    assert torch.allclose(stats[:5], (ref.double() ** 2).sum(-1).float(), rtol=1e-6)
