@@ -82,7 +82,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_la
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read", "pat_timing_fused_trace",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_gemm_norm", "pat_op_argmax",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
            "pat_kv_move_seconds", "pat_rms_length"]
 
@@ -138,7 +138,8 @@ def load_library() -> C.CDLL:
     lib.pat_op_gemm_plan.restype = C.c_int
     lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
-    lib.pat_op_embed_stats.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp, vp]
+    lib.pat_op_embed_stats.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
+    lib.pat_op_pack_act_gain.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.pat_op_gemm_norm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.c_int32, C.c_float, C.c_int32, vp, C.c_int32, vp]
     dp = C.POINTER(C.c_double)
     lib.pat_predictor_fit.argtypes = [C.POINTER(pat_grid_row), C.c_int32, C.POINTER(vp)]
@@ -395,24 +396,41 @@ def pat_op_rmsnorm_pack(x, g, eps):
     return hi, lo
 
 
-def pat_op_embed_stats(table, tok):
-    """table bf16 [vocab, h], tok int32 [b <= 16] (device) -> (x fp32 [16, h] with rows >= b unset, stats fp32 [16])."""
+def pat_op_embed_stats(table, tok, g):
+    """table bf16 [vocab, h], tok int32 [b <= 16], g bf16 [h] (device) -> (x fp32 [16, h] with rows >= b unset,
+    stats fp32 [16], packed x * g (hi, lo))."""
     import torch
+    lib = load_library()
     b, h = tok.shape[0], table.shape[1]
     x = torch.zeros(16, h, dtype=torch.float32, device=table.device)
     stats = torch.zeros(16, dtype=torch.float32, device=table.device)
-    rc = load_library().pat_op_embed_stats(_ptr(table), h, _ptr(tok), b, _ptr(x), _ptr(stats), _stream())
+    nbytes = lib.pat_op_packed_act_bytes(16, h)
+    hi = torch.zeros(nbytes, dtype=torch.uint8, device=table.device); lo = torch.zeros_like(hi)
+    rc = lib.pat_op_embed_stats(_ptr(table), h, _ptr(tok), _ptr(g), b, _ptr(x), _ptr(stats), _ptr(hi), _ptr(lo), _stream())
     if rc:
         raise PatError(rc, "pat_op_embed_stats")
-    return x, stats
+    return x, stats, hi, lo
 
 
-def pat_op_gemm_norm(w_packed, n, k, x, g, stats, eps, b):
-    """y [b, n] = RMSNorm(x[:b]; g, eps) W^T; x fp32 [16, k], stats fp32 [n_parts, 16] partial sums of squares."""
+def pat_op_pack_act_gain(x, g):
+    """x fp32 [b, k], g bf16 [k] -> packed split-bf16 of x * g (hi, lo)."""
     import torch
-    assert x.shape == (16, k) and x.is_contiguous() and stats.is_contiguous() and stats.numel() % 16 == 0
-    y = torch.empty(b, n, dtype=torch.float32, device=x.device)
-    rc = load_library().pat_op_gemm_norm(_ptr(w_packed), n, k, _ptr(x), _ptr(g), _ptr(stats), stats.numel() // 16, eps, b,
+    lib = load_library()
+    b, k = x.shape
+    nbytes = lib.pat_op_packed_act_bytes(b, k)
+    hi = torch.zeros(nbytes, dtype=torch.uint8, device=x.device); lo = torch.zeros_like(hi)
+    rc = lib.pat_op_pack_act_gain(_ptr(x.contiguous()), _ptr(g), b, k, _ptr(hi), _ptr(lo), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_pack_act_gain")
+    return hi, lo
+
+
+def pat_op_gemm_norm(w_packed, n, k, xg_hi, xg_lo, stats, eps, b):
+    """y [b, n] = RMSNorm(x; g, eps) W^T from the packed x * g and stats fp32 [n_parts, 16] partial sums of squares of x."""
+    import torch
+    assert stats.is_contiguous() and stats.numel() % 16 == 0
+    y = torch.empty(b, n, dtype=torch.float32, device=stats.device)
+    rc = load_library().pat_op_gemm_norm(_ptr(w_packed), n, k, _ptr(xg_hi), _ptr(xg_lo), _ptr(stats), stats.numel() // 16, eps, b,
                                          _ptr(y), n, _stream())
     if rc:
         raise PatError(rc, "pat_op_gemm_norm")

@@ -37,7 +37,7 @@ struct WorkLayout {   // byte offsets inside the work arena
     int64_t gemm_part_bytes;
     // fused layer kernel (live batch <= 16): three rotating residual buffers, packed o and SwiGLU outputs,
     // sums of squares, barrier words
-    int64_t xr[3], o_hi, o_lo, act_hi, act_lo, stats_e, stats1, stats2, sync;
+    int64_t xr[3], o_hi, o_lo, act_hi, act_lo, pk_hi[3], pk_lo[3], stats_e, stats1, stats2, sync;
 };
 
 struct WeightLayout {  // byte offsets inside the weights arena
@@ -174,6 +174,7 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     for (int i = 0; i < 3; ++i) w->xr[i] = take((int64_t)kFusedMaxBatch * s.H * 4);
     w->o_hi = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d)); w->o_lo = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d));
     w->act_hi = take(packed_x_bytes(kFusedMaxBatch, s.F)); w->act_lo = take(packed_x_bytes(kFusedMaxBatch, s.F));
+    for (int i = 0; i < 3; ++i) { w->pk_hi[i] = take(packed_x_bytes(kFusedMaxBatch, s.H)); w->pk_lo[i] = take(packed_x_bytes(kFusedMaxBatch, s.H)); }
     w->stats_e = take(16 * 4);
     w->stats1 = take((int64_t)cdiv(s.H, 16) * 16 * 4); w->stats2 = take((int64_t)cdiv(s.H, 16) * 16 * 4);
     w->sync = take((int64_t)kFusedSyncWords * 4);
@@ -680,23 +681,26 @@ static int run_layers_fused(pat_ctx *c, int B, int C, int64_t n_chunks, float *l
     fa.stats1 = at<float>(W, w.stats1); fa.stats2 = at<float>(W, w.stats2);
     fa.sync = at<unsigned>(W, w.sync); fa.max_spin = 400000u; fa.err = c->st.scalars + 7; fa.trace = c->fused_trace;
 
-    // the projection of layer `l` (or the head for l == NL) that closes a launch: RMSNorm of `x` with that layer's gains
-    auto set_next = [&](int l, const float *x, const float *stats, int parts) {
+    // the projection of layer `l` (or the head for l == NL) that closes a launch; its operand x * gains (packed) and
+    // the sums of squares of x come from the phase (or the embedding kernel) that produced x
+    auto gains_of = [&](int l) { return (const uint16_t *)(l < s.NL ? Wb + c->wt.layer0 + c->wt.layer_stride * l + c->wt.g1 : Wb + c->wt.gf); };
+    auto set_next = [&](int l, int pk, const float *stats, int parts) {
+        const uint4 *xh = at<uint4>(W, w.pk_hi[pk]), *xl = at<uint4>(W, w.pk_lo[pk]);
         if (l < s.NL) {
             char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
-            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, nullptr, nullptr, B, qkv, s.qkv_rows, nullptr, 0);
+            GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, xh, xl, B, qkv, s.qkv_rows, nullptr, 0);
             if (!c->cfg.qk_norm) {
                 g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = c->st.kv_len; g.row_slot = nullptr;
                 g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
                 fa.next_mode = kGemmQKV;
             } else fa.next_mode = kGemmStore;
             fa.next = g;
-            fa.n_next = NormIn{x, (const uint16_t *)(L + c->wt.g1), stats, parts, s.H, c->cfg.rms_eps};
         } else {
-            fa.next = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, nullptr, nullptr, B, logits, s.Vs, nullptr, 0);
+            fa.next = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, xh, xl, B, logits, s.Vs, nullptr, 0);
             fa.next_mode = kGemmStore;
-            fa.n_next = NormIn{x, (const uint16_t *)(Wb + c->wt.gf), stats, parts, s.H, c->cfg.rms_eps};
         }
+        fa.n_next = NormIn{stats, parts, s.H, c->cfg.rms_eps};
+        fa.g_next = gains_of(l);
     };
     // model family with per-head q/k normalisation: the plain projection is followed by the kernel that normalises, rotates and appends
     auto qk_norm_tail = [&](int l) -> int {
@@ -711,10 +715,11 @@ static int run_layers_fused(pat_ctx *c, int B, int C, int64_t n_chunks, float *l
 
     {   // embedding + its sums of squares, then the first layer's QKV alone
         TimeScope t(c, 2);
-        PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, X[0], at<float>(W, w.stats_e), st));
+        PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, gains_of(0), B, X[0], at<float>(W, w.stats_e),
+                                      at<uint4>(W, w.pk_hi[0]), at<uint4>(W, w.pk_lo[0]), st));
     }
     fa.p_begin = 4;
-    set_next(0, X[0], at<float>(W, w.stats_e), 1);
+    set_next(0, 0, at<float>(W, w.stats_e), 1);
     fa.gen0 = c->sync_gen;
     { TimeScope t(c, 0); PAT_HIP(c, launch_layer_fused(fa, c->n_cu, st)); }
     if (int rc = qk_norm_tail(0)) return rc;
@@ -729,11 +734,12 @@ static int run_layers_fused(pat_ctx *c, int B, int C, int64_t n_chunks, float *l
         fa.merge = aa;
         fa.x_in = x_in; fa.x1 = x1; fa.x2 = x2;
         fa.o = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, aa.ohi, aa.olo, B, nullptr, s.H, nullptr, 0);
-        fa.gu = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, nullptr, nullptr, B, nullptr, 0, nullptr, 0);
+        fa.gu = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, at<uint4>(W, w.pk_hi[1]), at<uint4>(W, w.pk_lo[1]), B, nullptr, 0, nullptr, 0);
         fa.gu.yhi = at<uint4>(W, w.act_hi); fa.gu.ylo = at<uint4>(W, w.act_lo); fa.gu.KS_out = s.F / 32;
-        fa.n_gu = NormIn{x1, (const uint16_t *)(L + c->wt.g2), fa.stats1, n_parts, s.H, c->cfg.rms_eps};
+        fa.n_gu = NormIn{fa.stats1, n_parts, s.H, c->cfg.rms_eps};
+        fa.g_gu = (const uint16_t *)(L + c->wt.g2);
         fa.down = gemm_args(L + c->wt.wd, s.H, s.F, fa.gu.yhi, fa.gu.ylo, B, nullptr, s.H, nullptr, 0);
-        set_next(l + 1, x2, fa.stats2, n_parts);
+        set_next(l + 1, 2, fa.stats2, n_parts);
         fa.gen0 = c->sync_gen;
         c->sync_gen += 4;                                   // merge | O | gate/up | down | next: four barriers
         { TimeScope t(c, 0); PAT_HIP(c, launch_layer_fused(fa, c->n_cu, st)); }
@@ -1184,16 +1190,24 @@ int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *x
     return launch_gemm(g, mode, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
-int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, int32_t b, float *x, float *stats, void *stream)
+int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, const void *g, int32_t b, float *x, float *stats, void *xg_hi,
+                       void *xg_lo, void *stream)
 {
-    if (!table || !tok || !x || !stats || h <= 0 || h % 32 || b <= 0 || b > kFusedMaxBatch) return PAT_EINVAL;
-    return launch_embed_stats((const uint16_t *)table, h, tok, b, x, stats, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+    if (!table || !tok || !g || !x || !stats || !xg_hi || !xg_lo || h <= 0 || h % 32 || b <= 0 || b > kFusedMaxBatch) return PAT_EINVAL;
+    return launch_embed_stats((const uint16_t *)table, h, tok, (const uint16_t *)g, b, x, stats, (uint4 *)xg_hi, (uint4 *)xg_lo,
+                              (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
-int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const float *x, const void *g, const float *stats, int32_t n_parts,
+int pat_op_pack_act_gain(const float *x, const void *g, int32_t b, int32_t k, void *xg_hi, void *xg_lo, void *stream)
+{
+    if (!x || !g || !xg_hi || !xg_lo || b <= 0 || k <= 0 || k % 32) return PAT_EINVAL;
+    return launch_pack_act_gain(x, (const uint16_t *)g, b, k, (uint4 *)xg_hi, (uint4 *)xg_lo, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+}
+
+int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const void *xg_hi, const void *xg_lo, const float *stats, int32_t n_parts,
                      float eps, int32_t b, float *y, int32_t ldy, void *stream)
 {
-    if (!w_packed || !x || !g || !stats || !y || n <= 0 || k <= 0 || k % 32 || n_parts < 1 || b <= 0 || b > kFusedMaxBatch || ldy < n)
+    if (!w_packed || !xg_hi || !xg_lo || !stats || !y || n <= 0 || k <= 0 || k % 32 || n_parts < 1 || b <= 0 || b > kFusedMaxBatch || ldy < n)
         return PAT_EINVAL;
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
@@ -1203,8 +1217,8 @@ int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const float *x,
     if (!usable) return PAT_ESTATE;
     FusedArgs fa{};
     fa.B = b; fa.H = k; fa.p_begin = 4; fa.next_mode = kGemmStore;
-    fa.next = gemm_args(w_packed, n, k, nullptr, nullptr, b, y, ldy, nullptr, 0);
-    fa.n_next = NormIn{x, (const uint16_t *)g, stats, n_parts, k, eps};
+    fa.next = gemm_args(w_packed, n, k, (const uint4 *)xg_hi, (const uint4 *)xg_lo, b, y, ldy, nullptr, 0);
+    fa.n_next = NormIn{stats, n_parts, k, eps};
     return launch_layer_fused(fa, n_cu, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 

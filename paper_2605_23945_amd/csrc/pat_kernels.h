@@ -80,11 +80,9 @@ hipError_t launch_attn_prefill(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnArgs &a, hipStream_t s);
 
 // ---- fused layer kernel for live batches <= 16 (layer_fused.hip) ------------------
-// fp32 rows whose RMSNorm is folded into a projection: scale 1 / sqrt(sum(x^2) / H + eps) from the per-part
-// sums of squares stats[part][16] (fixed summation order), times the gains g.
+// RMSNorm folded into a projection: the operand rows are x * gains (packed), the results are multiplied by
+// 1 / sqrt(sum(x^2) / H + eps) of their batch row, the sums given as per-part sums stats[part][16] (fixed order).
 struct NormIn {
-    const float *x;            // [16, H] (rows past the live batch are padding)
-    const uint16_t *g;         // [H] bf16
     const float *stats;        // [n_parts][16]
     int n_parts, H;
     float eps;
@@ -93,9 +91,10 @@ struct FusedArgs {
     int B, H;
     int p_begin;               // first phase to run: 0 merge, 1 O, 2 gate/up, 3 down, 4 next projection only
     int next_mode;             // kGemmQKV (next layer's QKV with rotary + append), kGemmStore (plain projection / head)
-    AttnArgs merge;            // P0: chunk partials -> packed o (merge.ohi / merge.olo)
-    GemmArgs o, gu, down, next;
-    NormIn n_gu, n_next;
+    AttnArgs merge;            // P0: chunk partials -> packed o (merge.ohi / merge.olo = o.xhi / o.xlo)
+    GemmArgs o, gu, down, next;   // their xhi / xlo are the packed operands: o (P0), x1 * g (P1), a (P2), x2 * g (P3)
+    NormIn n_gu, n_next;       // sums of squares of x1 / x2 (or of the embedding rows for the first launch of a step)
+    const uint16_t *g_gu, *g_next;   // gains of the RMSNorm before gate/up and before the next projection
     const float *x_in;         // residual before the O projection
     float *x1, *x2;            // residual after O / after down: each written in one phase only
     float *stats1, *stats2;    // per-tile sums of squares of x1 / x2: [H / 16][16]
@@ -109,7 +108,9 @@ constexpr int kFusedSyncWords = 2048;      // 8 KiB
 constexpr int kFusedMaxBatch = 16;
 hipError_t fused_prepare(int n_cu, bool *usable);
 hipError_t launch_layer_fused(const FusedArgs &fa, int n_wg, hipStream_t s);
-hipError_t launch_embed_stats(const uint16_t *table, int H, const int32_t *tok, int B, float *x, float *stats, hipStream_t s);
+hipError_t launch_embed_stats(const uint16_t *table, int H, const int32_t *tok, const uint16_t *gains, int B, float *x, float *stats,
+                              uint4 *pk_hi, uint4 *pk_lo, hipStream_t s);
+hipError_t launch_pack_act_gain(const float *x, const uint16_t *gains, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);
 hipError_t launch_sync_reset(unsigned *w, int n_words, hipStream_t s);
 
 // ---- small kernels (step_misc.hip) ----------------------------------------------

@@ -140,31 +140,38 @@ def test_argmax_bit_exact(pat, orc):
 @pytest.mark.parametrize("n,k,b", [(256, 1024, 1), (1040, 4096, 16), (512, 5120, 7), (96, 8192, 3), (2048, 256, 16), (4096, 4096, 2),
                                    (8000, 4096, 5)])
 def test_gemm_with_folded_rmsnorm_vs_oracle(pat, orc, n, k, b):
-    """The projection of the small-batch step: RMSNorm of fp32 rows folded into the operand load, the rows' sums of
-    squares supplied as per-16-column partial sums (what the producing projection writes).  Rows past the live
-    batch are padding and must not leak into any result (they are filled with NaN here)."""
+    """The projection of the small-batch step: the operand is x * gains (packed by the producer of x), the rows' sums
+    of squares arrive as per-16-column partial sums (what the producing projection writes) and the result is scaled
+    by 1 / rms.  Rows past the live batch are padding and must not leak into any result (NaN here)."""
     w, x = _w(n, k, 7 + n + k), _x(b, k, 3 * n + b) * 3.0
     g = pi.normal_bf16(pi.stream_key(1, 3), torch.arange(k, dtype=torch.int64), 0.02, 1.0)
     x16 = torch.full((16, k), float("nan"))
     x16[:b] = x
     stats = (x16.view(16, k // 16, 16) ** 2).sum(-1).T.contiguous()           # [k / 16, 16]
     wp = pat.pat_op_pack_weight(w.to(DEV))
-    y = pat.pat_op_gemm_norm(wp, n, k, x16.to(DEV), g.to(DEV), stats.to(DEV), 1e-6, b).cpu().double().numpy()
+    hi, lo = pat.pat_op_pack_act_gain(x16.to(DEV), g.to(DEV))
+    y = pat.pat_op_gemm_norm(wp, n, k, hi, lo, stats.to(DEV), 1e-6, b).cpu().double().numpy()
     assert np.all(np.isfinite(y))
     for r in sorted(set([0, b - 1, b // 2])):
         ref = orc.matvec(bits(w), orc.rmsnorm(x[r].double().numpy(), bits(g), 1e-6))
         scale = float(np.sqrt(np.mean(ref * ref)))
         assert np.max(np.abs(y[r] - ref)) <= 1e-4 * scale
     # one part per row (as after the embedding) gives the same 1/rms up to the summation order
-    y1 = pat.pat_op_gemm_norm(wp, n, k, x16.to(DEV), g.to(DEV), torch.nan_to_num((x16 ** 2).sum(-1), nan=0.0).to(DEV), 1e-6, b)
+    y1 = pat.pat_op_gemm_norm(wp, n, k, hi, lo, torch.nan_to_num((x16 ** 2).sum(-1), nan=0.0).to(DEV), 1e-6, b)
     assert np.max(np.abs(y1.cpu().double().numpy() - y)) <= 1e-5 * float(np.sqrt(np.mean(y * y)))
 
 
-def test_embed_stats_rows_and_sums(pat):
+def test_embed_stats_rows_sums_and_packed_operand(pat):
     s = pi.CONFIGS["tiny_tp1"]["shard"]
     table = pi.embedding_table(s, device=DEV)
+    g = pi.layer_weights(s, 0, device=DEV)["g1"]
     tok = torch.tensor([5, 0, 1023, 77, 5], dtype=torch.int32, device=DEV)
-    x, stats = pat.pat_op_embed_stats(table, tok)
+    x, stats, hi, lo = pat.pat_op_embed_stats(table, tok, g)
     ref = table[tok.long()].float()
     assert torch.equal(x[:5], ref)
     assert torch.allclose(stats[:5], (ref.double() ** 2).sum(-1).float(), rtol=1e-6)
+    got = pat.unpack_act(hi, lo, 16, s.hidden)[:5]
+    want = (ref.double() * g.double()[None, :]).cpu().numpy()
+    assert np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-30)) <= 2.0 ** -16
+    hi2, lo2 = pat.pat_op_pack_act_gain(x[:5].contiguous(), g)                 # the stand-alone packing agrees bit for bit
+    assert np.array_equal(pat.unpack_act(hi2, lo2, 5, s.hidden), got)
