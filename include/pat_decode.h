@@ -290,21 +290,24 @@ int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *x
 /* RMSNorm of x [b, h] with gains g [h] bf16 into packed split-bf16 activations. */
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo,
                         void *hip_stream);
-/* The operators of the small-batch step's projections with a folded RMSNorm (live batch <= 16): the producer of
+/* The operators of the small-batch step's projections with a folded RMSNorm (live batch <= 32): the producer of
  * the rows x hands over x * gains as a packed split-bf16 operand plus the rows' sums of squares, and the
- * projection multiplies its results by 1 / sqrt(sum(x^2) / k + eps) of their batch row.
+ * projection multiplies its results by 1 / sqrt(sum(x^2) / k + eps) of their batch row.  R = 16 * ceil(b / 16).
  *   pat_op_embed_stats: x[b, h] fp32 = rows tok[i] of a bf16 [vocab, h] table, stats[i] = sum of squares of row i,
- *     xg_hi / xg_lo = x * g packed (tok device int32[b]; g device bf16[h]; stats device float[16]; the packed
- *     buffers pat_op_packed_act_bytes(16, h) bytes each);
+ *     xg_hi / xg_lo = x * g packed (tok device int32[b]; g device bf16[h]; stats device float[R]; the packed
+ *     buffers pat_op_packed_act_bytes(b, h) bytes each);
  *   pat_op_pack_act_gain: the packed x * g of any fp32 rows x [b, k];
  *   pat_op_gemm_norm: y[b, n] = RMSNorm(x; g, eps) W^T with W [n, k] in streaming layout, from x * g packed and the
- *     rows' sums of squares given as n_parts partial sums stats[part][16] that are added in a fixed order
- *     (n_parts = 1 after pat_op_embed_stats).  b <= 16.  PAT_ESTATE if the device cannot hold the kernel. */
+ *     rows' sums of squares given as n_parts partial sums stats[part][R] that are added in a fixed order
+ *     (n_parts = 1 after pat_op_embed_stats).  fused = 0: the small-batch streaming kernel (b <= 32); fused = 1:
+ *     the projection phase of the fused layer kernel (b <= 16; PAT_ESTATE if the device cannot hold it).
+ *   pat_decode_uses_fused_kernel: 1 if steps of this context at live batch <= 16 run the fused layer kernel. */
 int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, const void *g, int32_t b, float *x, float *stats,
                        void *xg_hi, void *xg_lo, void *hip_stream);
 int pat_op_pack_act_gain(const float *x, const void *g, int32_t b, int32_t k, void *xg_hi, void *xg_lo, void *hip_stream);
 int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const void *xg_hi, const void *xg_lo, const float *stats,
-                     int32_t n_parts, float eps, int32_t b, float *y, int32_t ldy, void *hip_stream);
+                     int32_t n_parts, float eps, int32_t b, float *y, int32_t ldy, int32_t fused, void *hip_stream);
+int pat_decode_uses_fused_kernel(pat_ctx *ctx);
 /* (max, lowest index) per row of logits [b, n]; out_idx[b] = base + index. NaN counts as -inf. */
 int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val,
                   void *hip_stream);

@@ -82,7 +82,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_la
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read", "pat_timing_fused_trace",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_op_argmax",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_decode_uses_fused_kernel", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
            "pat_kv_move_seconds", "pat_rms_length"]
 
@@ -140,7 +140,8 @@ def load_library() -> C.CDLL:
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     lib.pat_op_embed_stats.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
     lib.pat_op_pack_act_gain.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
-    lib.pat_op_gemm_norm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.c_int32, C.c_float, C.c_int32, vp, C.c_int32, vp]
+    lib.pat_op_gemm_norm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.c_int32, C.c_float, C.c_int32, vp, C.c_int32, C.c_int32, vp]
+    lib.pat_decode_uses_fused_kernel.argtypes = [vp]
     dp = C.POINTER(C.c_double)
     lib.pat_predictor_fit.argtypes = [C.POINTER(pat_grid_row), C.c_int32, C.POINTER(vp)]
     lib.pat_predictor_destroy.argtypes = [vp]
@@ -328,6 +329,9 @@ class Decoder:
     def pat_timing_enable(self, on: bool):
         self._chk(self.lib.pat_timing_enable(self.ctx, int(on)))
 
+    def pat_decode_uses_fused_kernel(self) -> bool:
+        return bool(self.lib.pat_decode_uses_fused_kernel(self.ctx))
+
     def pat_timing_fused_trace(self, trace):
         """trace: int64 device tensor of 256 x 16 words (or None to switch the stamps off)."""
         self._chk(self.lib.pat_timing_fused_trace(self.ctx, _ptr(trace)))
@@ -397,14 +401,15 @@ def pat_op_rmsnorm_pack(x, g, eps):
 
 
 def pat_op_embed_stats(table, tok, g):
-    """table bf16 [vocab, h], tok int32 [b <= 16], g bf16 [h] (device) -> (x fp32 [16, h] with rows >= b unset,
-    stats fp32 [16], packed x * g (hi, lo))."""
+    """table bf16 [vocab, h], tok int32 [b <= 32], g bf16 [h] (device) -> (x fp32 [R, h] with rows >= b unset,
+    stats fp32 [R], packed x * g (hi, lo)); R = 16 * ceil(b / 16)."""
     import torch
     lib = load_library()
     b, h = tok.shape[0], table.shape[1]
-    x = torch.zeros(16, h, dtype=torch.float32, device=table.device)
-    stats = torch.zeros(16, dtype=torch.float32, device=table.device)
-    nbytes = lib.pat_op_packed_act_bytes(16, h)
+    R = (b + 15) // 16 * 16
+    x = torch.zeros(R, h, dtype=torch.float32, device=table.device)
+    stats = torch.zeros(R, dtype=torch.float32, device=table.device)
+    nbytes = lib.pat_op_packed_act_bytes(R, h)
     hi = torch.zeros(nbytes, dtype=torch.uint8, device=table.device); lo = torch.zeros_like(hi)
     rc = lib.pat_op_embed_stats(_ptr(table), h, _ptr(tok), _ptr(g), b, _ptr(x), _ptr(stats), _ptr(hi), _ptr(lo), _stream())
     if rc:
@@ -425,13 +430,15 @@ def pat_op_pack_act_gain(x, g):
     return hi, lo
 
 
-def pat_op_gemm_norm(w_packed, n, k, xg_hi, xg_lo, stats, eps, b):
-    """y [b, n] = RMSNorm(x; g, eps) W^T from the packed x * g and stats fp32 [n_parts, 16] partial sums of squares of x."""
+def pat_op_gemm_norm(w_packed, n, k, xg_hi, xg_lo, stats, eps, b, fused=False):
+    """y [b, n] = RMSNorm(x; g, eps) W^T from the packed x * g and stats fp32 [n_parts, R] partial sums of squares of x
+    (R = 16 * ceil(b / 16)); fused: through the fused layer kernel's projection phase instead of the streaming kernel."""
     import torch
-    assert stats.is_contiguous() and stats.numel() % 16 == 0
+    R = (b + 15) // 16 * 16
+    assert stats.is_contiguous() and stats.numel() % R == 0
     y = torch.empty(b, n, dtype=torch.float32, device=stats.device)
-    rc = load_library().pat_op_gemm_norm(_ptr(w_packed), n, k, _ptr(xg_hi), _ptr(xg_lo), _ptr(stats), stats.numel() // 16, eps, b,
-                                         _ptr(y), n, _stream())
+    rc = load_library().pat_op_gemm_norm(_ptr(w_packed), n, k, _ptr(xg_hi), _ptr(xg_lo), _ptr(stats), stats.numel() // R, eps, b,
+                                         _ptr(y), n, int(bool(fused)), _stream())
     if rc:
         raise PatError(rc, "pat_op_gemm_norm")
     return y

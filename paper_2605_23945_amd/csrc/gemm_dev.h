@@ -29,6 +29,18 @@ __device__ __forceinline__ floatx4_t mfma16(u32x4_t a, u32x4_t b, floatx4_t c)
                                                    0, 0, 0);
 }
 
+// The sum of the two accumulators of a tile (hi and lo operand terms), pinned to the place where it is written:
+// the empty asm takes the four sums as operands, so the additions cannot be moved below a later branch.  They
+// must stay in the basic block of the matrix instructions: the compiler pads the distance from a matrix
+// instruction to the first read of its result only inside a block, and a read that was sunk behind a branch
+// picked up a stale element now and then (seen on the second batch tile of the 17..32-row kernel).
+__device__ __forceinline__ float4 mfma_sum_pinned(floatx4_t h, floatx4_t l)
+{
+    float x = h[0] + l[0], y = h[1] + l[1], z = h[2] + l[2], w = h[3] + l[3];
+    asm volatile("" : "+v"(x), "+v"(y), "+v"(z), "+v"(w));
+    return make_float4(x, y, z, w);
+}
+
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + expf(-z)); }
 
 // Epilogue for a float4 = 4 consecutive output features (rows 16 rt + 4 quad ..) of batch row b.
@@ -89,6 +101,23 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, int rt, int qua
                 o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
             }
             *reinterpret_cast<float4 *>(yp) = o;
+            if (MODE == kGemmAccum && a.ngains != nullptr) {
+                // hand-over to the projection that consumes RMSNorm(y): y * gains packed, and the tile's sum of squares
+                // of this batch row (the four lanes of a row hold four columns each: (q0 + q1) + (q2 + q3))
+                const uint2 gv = *reinterpret_cast<const uint2 *>(a.ngains + n);
+                uint16_t h[4], l[4];
+                split_bf16(o.x * bf16lo(gv.x), h[0], l[0]); split_bf16(o.y * bf16hi(gv.x), h[1], l[1]);
+                split_bf16(o.z * bf16lo(gv.y), h[2], l[2]); split_bf16(o.w * bf16hi(gv.y), h[3], l[3]);
+                const int64_t off = packed_elem_offset(b, n, a.n_tiles >> 1);      // the consumer's K is this projection's N
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.npk_hi) + off) =
+                    make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.npk_lo) + off) =
+                    make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+                float ss = (o.x * o.x + o.y * o.y) + (o.z * o.z + o.w * o.w);
+                ss = ss + __shfl_xor(ss, 16, 64);
+                ss = ss + __shfl_xor(ss, 32, 64);
+                if (quad == 0) a.nstats[(int64_t)rt * (((a.B + 15) >> 4) << 4) + b] = ss;
+            }
         } else {
             const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

@@ -84,13 +84,15 @@ __device__ __forceinline__ void xs_pass(const GemmArgs &a, int lane, int wave, i
                 acc_l[nb] = mfma16(w[u], xl[u][nb], acc_l[nb]);
             }
         }
+        // every accumulator is read here, in the block of the matrix instructions and before any branch (see mfma_sum_pinned)
+        float4 v[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) v[nb] = mfma_sum_pinned(acc_h[nb], acc_l[nb]);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            float4 v = make_float4(acc_h[nb][0] + acc_l[nb][0], acc_h[nb][1] + acc_l[nb][1], acc_h[nb][2] + acc_l[nb][2],
-                                   acc_h[nb][3] + acc_l[nb][3]);
             float4 *slot = &red[((i * WAVES + wave) * NB + nb) * 64 + lane];    // this wave's own slot
-            if (!first) { const float4 o = *slot; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
-            *slot = v;
+            if (!first) { const float4 o = *slot; v[nb].x += o.x; v[nb].y += o.y; v[nb].z += o.z; v[nb].w += o.w; }
+            *slot = v[nb];
         }
     }
 }
@@ -99,6 +101,8 @@ template <int NB, int UK, int TB, int kXsWaves, int MODE>
 __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 {
     extern __shared__ float4 red[];   // [TB][kXsWaves][NB][64]
+    constexpr int R = 16 * NB, PQ = R / 4;          // batch rows of the tiles, 16-byte pieces per part of the row statistics
+    __shared__ __align__(16) float s_part[kXsWaves][R];
     // the wave index as a scalar: what derives from it (k share, slots, tile) stays in scalar registers
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KS = a.KS, Rg = a.Rg;
@@ -106,6 +110,22 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
     // the wave's contiguous share of the k-steps (shares differ by at most one step)
     const int kown0 = (int)((int64_t)wave * KS / kXsWaves), kown1 = (int)((int64_t)(wave + 1) * KS / kXsWaves);
     const int rt0 = (int)((int64_t)rg * a.n_tiles / Rg), rt1 = (int)((int64_t)(rg + 1) * a.n_tiles / Rg);
+
+    // Folded RMSNorm (a.sstats set): the operand rows are x * gains, the results are multiplied by 1 / rms of their
+    // batch row.  The rows' sums of squares come as per-part sums sstats[part][R]; the workgroup adds them once, in
+    // a fixed order: thread t takes the 16-byte pieces t, t + threads, ... (four rows of one part) in increasing
+    // order, a wave folds its pieces per row group with a shuffle butterfly, and the wave sums meet in LDS at the
+    // barrier the first tile group has anyway.
+    const bool scale = a.sstats != nullptr;
+    float4 ssq = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (scale)
+        for (int i = threadIdx.x; i < a.s_parts * PQ; i += kXsWaves * 64) {
+            const float4 t = reinterpret_cast<const float4 *>(a.sstats)[i];
+            ssq.x += t.x; ssq.y += t.y; ssq.z += t.z; ssq.w += t.w;
+        }
+    float inv[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) inv[nb] = 1.f;
 
     for (int tb0 = rt0; tb0 < rt1; tb0 += TB) {
         const int nt = min(TB, rt1 - tb0);
@@ -125,7 +145,25 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
             }
             k = kown1;
         }
+        if (scale && tb0 == rt0) {
+#pragma unroll
+            for (int off = PQ; off < 64; off <<= 1) {
+                ssq.x += __shfl_xor(ssq.x, off, 64); ssq.y += __shfl_xor(ssq.y, off, 64);
+                ssq.z += __shfl_xor(ssq.z, off, 64); ssq.w += __shfl_xor(ssq.w, off, 64);
+            }
+            if (lane < PQ) *reinterpret_cast<float4 *>(&s_part[wave][lane * 4]) = ssq;
+        }
         __syncthreads();
+        if (scale && tb0 == rt0) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int row = min(nb * 16 + (lane & 15), a.B - 1);
+                float tot = 0.f;
+#pragma unroll
+                for (int w = 0; w < kXsWaves; ++w) tot += s_part[w][row];
+                inv[nb] = 1.0f / sqrtf(tot / (float)a.s_h + a.s_eps);
+            }
+        }
         if (wave < nt) {
             // D tile layout: lane l holds rows (l/16)*4 .. +3 of column l%16 = 4 consecutive
             // output features of one batch row.  Waves with an empty share left no partial.
@@ -147,6 +185,7 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
                         v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
                     }
                 }
+                if (scale) { v.x *= inv[nb]; v.y *= inv[nb]; v.z *= inv[nb]; v.w *= inv[nb]; }
                 gemm_epilogue<MODE>(a, rt, lane >> 4, nb * 16 + (lane & 15), v);
             }
         }
@@ -537,6 +576,8 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     GemmArgs a = a0;
     const GemmPlan p = gemm_plan(a.n_tiles, a.KS, a.B);
     a.Kb = p.Kb; a.Rg = p.Rg;
+    if ((a.ngains != nullptr || a.sstats != nullptr) && a.B > 32) return hipErrorInvalidValue;      // folded RMSNorm: small-batch kernels only
+    if (a.ngains != nullptr && (a.n_valid % 32 != 0 || !a.npk_hi || !a.npk_lo || !a.nstats)) return hipErrorInvalidValue;
     if (a.Kb > 1 && (a.part == nullptr || (int64_t)a.Kb * a.B * a.n_tiles * 64 > a.part_bytes)) return hipErrorInvalidValue;
     // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
     if (a.B <= 32) { const hipError_t e = gemm_prepare_device(); if (e != hipSuccess) return e; }

@@ -211,7 +211,7 @@ __device__ __forceinline__ void fused_pass(const GemmArgs &a, int lane, int wave
         floatx4_t acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < U; ++u) { acc_h = mfma16(w[u], xh[u], acc_h); acc_l = mfma16(w[u], xl[u], acc_l); }
-        float4 v = make_float4(acc_h[0] + acc_l[0], acc_h[1] + acc_l[1], acc_h[2] + acc_l[2], acc_h[3] + acc_l[3]);
+        float4 v = mfma_sum_pinned(acc_h, acc_l);
         float4 *slot = &red[(i * kFW + wave) * 64 + lane];
         if (!first) { const float4 o = *slot; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
         *slot = v;
@@ -247,7 +247,7 @@ __device__ __forceinline__ void head_tile(const GemmArgs &a, const W8 &wp, int l
     PAT_HEAD_MMA(0, wp.v0) PAT_HEAD_MMA(1, wp.v1) PAT_HEAD_MMA(2, wp.v2) PAT_HEAD_MMA(3, wp.v3)
     PAT_HEAD_MMA(4, wp.v4) PAT_HEAD_MMA(5, wp.v5) PAT_HEAD_MMA(6, wp.v6) PAT_HEAD_MMA(7, wp.v7)
 #undef PAT_HEAD_MMA
-    red[wave * 64 + lane] = make_float4(acc_h[0] + acc_l[0], acc_h[1] + acc_l[1], acc_h[2] + acc_l[2], acc_h[3] + acc_l[3]);
+    red[wave * 64 + lane] = mfma_sum_pinned(acc_h, acc_l);
 }
 
 struct AccumOut { const float *x_in; float *x_out, *stats; const uint16_t *gains; uint4 *pk_hi, *pk_lo; };
@@ -455,7 +455,7 @@ hipError_t launch_layer_fused(const FusedArgs &fa, int n_wg, hipStream_t s)
 hipError_t launch_embed_stats(const uint16_t *table, int H, const int32_t *tok, const uint16_t *gains, int B, float *x, float *stats,
                               uint4 *pk_hi, uint4 *pk_lo, hipStream_t s)
 {
-    if (B <= 0 || B > 16) return hipErrorInvalidValue;
+    if (B <= 0) return hipErrorInvalidValue;
     embed_stats_kernel<<<B, 256, 0, s>>>(table, H, tok, gains, x, stats, pk_hi, pk_lo);
     return hipGetLastError();
 }

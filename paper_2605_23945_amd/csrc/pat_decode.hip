@@ -37,7 +37,7 @@ struct WorkLayout {   // byte offsets inside the work arena
     int64_t gemm_part_bytes;
     // fused layer kernel (live batch <= 16): three rotating residual buffers, packed o and SwiGLU outputs,
     // sums of squares, barrier words
-    int64_t xr[3], o_hi, o_lo, act_hi, act_lo, pk_hi[3], pk_lo[3], stats_e, stats1, stats2, sync;
+    int64_t xr[3], o_hi, o_lo, act_hi, act_lo, pk_hi[3], pk_lo[3], stats_e, stats1, stats2, sync, nstats;
 };
 
 struct WeightLayout {  // byte offsets inside the weights arena
@@ -175,7 +175,8 @@ void layouts(const pat_cfg *c, const Shard &s, WorkLayout *w, WeightLayout *wt, 
     w->o_hi = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d)); w->o_lo = take(packed_x_bytes(kFusedMaxBatch, s.hq * s.d));
     w->act_hi = take(packed_x_bytes(kFusedMaxBatch, s.F)); w->act_lo = take(packed_x_bytes(kFusedMaxBatch, s.F));
     for (int i = 0; i < 3; ++i) { w->pk_hi[i] = take(packed_x_bytes(kFusedMaxBatch, s.H)); w->pk_lo[i] = take(packed_x_bytes(kFusedMaxBatch, s.H)); }
-    w->stats_e = take(16 * 4);
+    w->stats_e = take(32 * 4);
+    w->nstats = take((int64_t)cdiv(s.H, 16) * 32 * 4);    // per-tile sums of squares of the residual rows, live batch <= 32
     w->stats1 = take((int64_t)cdiv(s.H, 16) * 16 * 4); w->stats2 = take((int64_t)cdiv(s.H, 16) * 16 * 4);
     w->sync = take((int64_t)kFusedSyncWords * 4);
     w->max_chunks = c->kv_token_budget / kMinChunk + 2 * (int64_t)MB;
@@ -309,6 +310,9 @@ int pick_chunk(const pat_ctx *c, int64_t *n_chunks)
     *n_chunks = best_n;
     return best;
 }
+
+// Up to 32 rows (one launch of the small-batch projection kernel) every RMSNorm is folded into its neighbours.
+inline bool norm_is_folded(int rows) { return rows <= 32; }
 
 }  // namespace
 
@@ -605,6 +609,21 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
     uint4 *a_hi = at<uint4>(W, w.a_hi), *a_lo = at<uint4>(W, w.a_lo), *b_hi = at<uint4>(W, w.b_hi), *b_lo = at<uint4>(W, w.b_lo);
     char *Wb = at<char>(c->bufs.weights, 0);
     float *gpart = at<float>(W, w.gemm_part);
+    // Up to 32 rows every RMSNorm is folded into its neighbours: the projection that produces the residual rows
+    // (or the embedding kernel) also writes rows * gains as the packed operand (a_hi / a_lo) and the rows' sums
+    // of squares, and the consuming projection scales its results by 1 / rms: six launches per layer, not eight.
+    const bool fold = norm_is_folded(B);
+    float *nstats = at<float>(W, w.nstats);
+    const int n_parts = cdiv(s.H, 16);
+    auto consume = [&](GemmArgs &g, bool after_embedding) {
+        if (!fold) return;
+        g.sstats = after_embedding ? at<float>(W, w.stats_e) : nstats;
+        g.s_parts = after_embedding ? 1 : n_parts; g.s_h = s.H; g.s_eps = c->cfg.rms_eps;
+    };
+    auto produce = [&](GemmArgs &g, const void *gains) {
+        if (!fold) return;
+        g.ngains = (const uint16_t *)gains; g.npk_hi = a_hi; g.npk_lo = a_lo; g.nstats = nstats;
+    };
     AttnArgs aa{};
     aa.kv = c->kv; aa.qkv = qkv; aa.ldq = s.qkv_rows; aa.hq = s.hq; aa.B = B; aa.kv_len = pos; aa.row_slot = row_slot;
     aa.page_table = c->st.page_table; aa.max_pages = s.max_pages; aa.chunk_start = c->st.chunk_start; aa.chunk_meta = c->st.chunk_meta; aa.chunk_tokens = C;
@@ -613,9 +632,10 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
 
     for (int l = 0; l < s.NL; ++l) {
         char *L = Wb + c->wt.layer0 + c->wt.layer_stride * l;
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        if (!fold) { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g1), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {   // QKV projection; its epilogue rotates q and k and appends k, v to the cache
             GemmArgs g = gemm_args(L + c->wt.wqkv, s.qkv_rows, s.H, a_hi, a_lo, B, qkv, s.qkv_rows, gpart, w.gemm_part_bytes);
+            consume(g, l == 0);
             if (!c->cfg.qk_norm) {
                 g.kv = c->kv; g.layer = l; g.hq = s.hq; g.max_pages = s.max_pages; g.kv_len = pos; g.row_slot = row_slot;
                 g.page_table = c->st.page_table; g.rope_cs = at<float>(W, w.rope);
@@ -639,16 +659,19 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
         }
         {
             GemmArgs g = gemm_args(L + c->wt.wo, s.H, s.hq * s.d, b_hi, b_lo, B, x, s.H, gpart, w.gemm_part_bytes);
+            produce(g, L + c->wt.g2);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        if (!fold) { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(L + c->wt.g2), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
             GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart, w.gemm_part_bytes);
             g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
+            consume(g, false);
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
         }
         {
             GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart, w.gemm_part_bytes);
+            produce(g, l + 1 < s.NL ? Wb + c->wt.layer0 + c->wt.layer_stride * (l + 1) + c->wt.g1 : Wb + c->wt.gf);   // the next RMSNorm's gains
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmAccum, st));
         }
     }
@@ -782,11 +805,21 @@ int pat_decode_step(pat_ctx *c, pat_step_report *report_host, int32_t *next_tok_
     if (B <= kFusedMaxBatch && c->fused_ok) {
         if (int rc = run_layers_fused(c, B, C, n_chunks, logits)) return rc;
     } else {
-        { TimeScope t(c, 2); PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st)); }
+        const bool fold = norm_is_folded(B);
+        const uint16_t *g0 = (const uint16_t *)(s.NL > 0 ? Wb + c->wt.layer0 + c->wt.g1 : Wb + c->wt.gf);     // gains of the first RMSNorm
+        {
+            TimeScope t(c, 2);
+            if (fold) PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, g0, B, x, at<float>(W, w.stats_e), a_hi, a_lo, st));
+            else PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, c->st.tok, B, x, st));
+        }
         if (int rc = run_layers(c, B, C, n_chunks, c->st.kv_len, nullptr, 0)) return rc;
-        { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
+        if (!fold) { TimeScope t(c, 2); PAT_HIP(c, launch_rmsnorm_pack(x, (const uint16_t *)(Wb + c->wt.gf), B, s.H, c->cfg.rms_eps, a_hi, a_lo, st)); }
         {
             GemmArgs g = gemm_args(Wb + c->wt.wlm, s.Vs, s.H, a_hi, a_lo, B, logits, s.Vs, gpart, w.gemm_part_bytes);
+            if (fold) {
+                g.sstats = s.NL > 0 ? at<float>(W, w.nstats) : at<float>(W, w.stats_e);
+                g.s_parts = s.NL > 0 ? cdiv(s.H, 16) : 1; g.s_h = s.H; g.s_eps = c->cfg.rms_eps;
+            }
             TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmStore, st));
         }
     }
@@ -876,7 +909,10 @@ int pat_prefill(pat_ctx *c, int32_t n, const int32_t *slots, const int32_t *toke
             PAT_HIP(c, hipMemcpyAsync(rows + a * MB, p + a * MB, (size_t)R * 4, hipMemcpyHostToDevice, c->stream));
         PAT_HIP(c, hipMemcpyAsync(c->st.chunk_meta, rec, (size_t)n_rec * 32, hipMemcpyHostToDevice, c->stream));
         PAT_HIP(c, launch_plan_rows(c->st, R, C, rows + MB, rows + 2 * MB, false, c->stream));
-        PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, rows, R, at<float>(W, c->wl.x), c->stream));
+        if (norm_is_folded(R))
+            PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, rows, (const uint16_t *)(Wb + c->wt.layer0 + c->wt.g1), R, at<float>(W, c->wl.x),
+                                          at<float>(W, c->wl.stats_e), at<uint4>(W, c->wl.a_hi), at<uint4>(W, c->wl.a_lo), c->stream));
+        else PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, rows, R, at<float>(W, c->wl.x), c->stream));
         if (int rc = run_layers(c, R, C, chunks, rows + 2 * MB, rows + MB, n_rec)) return rc;
         PAT_HIP(c, hipStreamSynchronize(c->stream));     // the staging buffers are reused by the next pass
     }
@@ -1193,7 +1229,7 @@ int pat_op_gemm_static(const void *w_packed, int32_t n, int32_t k, const void *x
 int pat_op_embed_stats(const void *table, int32_t h, const int32_t *tok, const void *g, int32_t b, float *x, float *stats, void *xg_hi,
                        void *xg_lo, void *stream)
 {
-    if (!table || !tok || !g || !x || !stats || !xg_hi || !xg_lo || h <= 0 || h % 32 || b <= 0 || b > kFusedMaxBatch) return PAT_EINVAL;
+    if (!table || !tok || !g || !x || !stats || !xg_hi || !xg_lo || h <= 0 || h % 32 || b <= 0 || b > 32) return PAT_EINVAL;
     return launch_embed_stats((const uint16_t *)table, h, tok, (const uint16_t *)g, b, x, stats, (uint4 *)xg_hi, (uint4 *)xg_lo,
                               (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
@@ -1205,10 +1241,15 @@ int pat_op_pack_act_gain(const float *x, const void *g, int32_t b, int32_t k, vo
 }
 
 int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const void *xg_hi, const void *xg_lo, const float *stats, int32_t n_parts,
-                     float eps, int32_t b, float *y, int32_t ldy, void *stream)
+                     float eps, int32_t b, float *y, int32_t ldy, int32_t fused, void *stream)
 {
-    if (!w_packed || !xg_hi || !xg_lo || !stats || !y || n <= 0 || k <= 0 || k % 32 || n_parts < 1 || b <= 0 || b > kFusedMaxBatch || ldy < n)
-        return PAT_EINVAL;
+    if (!w_packed || !xg_hi || !xg_lo || !stats || !y || n <= 0 || k <= 0 || k % 32 || n_parts < 1 || b <= 0 || ldy < n) return PAT_EINVAL;
+    if (b > (fused ? kFusedMaxBatch : 32)) return PAT_EINVAL;
+    GemmArgs g = gemm_args(w_packed, n, k, (const uint4 *)xg_hi, (const uint4 *)xg_lo, b, y, ldy, nullptr, 0);
+    if (!fused) {
+        g.sstats = stats; g.s_parts = n_parts; g.s_h = k; g.s_eps = eps;
+        return launch_gemm(g, kGemmStore, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
+    }
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
         return PAT_EHIP;
@@ -1217,10 +1258,12 @@ int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const void *xg_
     if (!usable) return PAT_ESTATE;
     FusedArgs fa{};
     fa.B = b; fa.H = k; fa.p_begin = 4; fa.next_mode = kGemmStore;
-    fa.next = gemm_args(w_packed, n, k, (const uint4 *)xg_hi, (const uint4 *)xg_lo, b, y, ldy, nullptr, 0);
+    fa.next = g;
     fa.n_next = NormIn{stats, n_parts, k, eps};
     return launch_layer_fused(fa, n_cu, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
+
+int pat_decode_uses_fused_kernel(pat_ctx *c) { return c && c->fused_ok ? 1 : 0; }
 
 int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, float eps, void *xhi, void *xlo, void *stream)
 {

@@ -33,6 +33,13 @@ struct GemmArgs {
     const int32_t *kv_len, *page_table;
     const int32_t *row_slot;   // slot (page-table row) of batch row b, or NULL: slot b
     const float *rope_cs;      // [pos][d/2][cos, sin]
+    // RMSNorm folded into the small-batch projections (live batch <= 32), both NULL-able:
+    //  * producer side (kGemmAccum): besides y += ..., write y * gains as the packed split-bf16 operand of the
+    //    projection that consumes RMSNorm(y), and the tile's sums of squares of y: nstats[tile][16 * batch tiles];
+    //  * consumer side (any mode): the operand is such an x * gains; results are multiplied by 1 / rms of their
+    //    batch row, from the per-part sums of squares sstats[part][16 * batch tiles] (fixed summation order).
+    const uint16_t *ngains; uint4 *npk_hi, *npk_lo; float *nstats;
+    const float *sstats; int s_parts, s_h; float s_eps;
     float *part;               // scratch for K-slice partials [Kb][B][n_tiles * 16], or NULL
     int64_t part_bytes;        // its size: a plan that needs more is refused
     int Kb, Rg;                // set by launch_gemm from gemm_plan

@@ -94,7 +94,8 @@ def test_kv_append_bytes_are_the_rounding_of_the_projection_output(orc, hq, hkv,
     w = pi.layer_weights(shard, 0, device=DEV)
     table = pi.embedding_table(shard, device=DEV)
     x, stats, xg_hi, xg_lo = pat.pat_op_embed_stats(table, torch.as_tensor(req["token"], dtype=torch.int32, device=DEV), w["g1"])
-    y = pat.pat_op_gemm_norm(pat.pat_op_pack_weight(w["wqkv"]), shard.qkv_rows, H, xg_hi, xg_lo, stats, m.rms_eps, n)
+    y = pat.pat_op_gemm_norm(pat.pat_op_pack_weight(w["wqkv"]), shard.qkv_rows, H, xg_hi, xg_lo, stats, m.rms_eps, n,
+                             fused=dec.pat_decode_uses_fused_kernel())
     y = y.cpu().numpy()
     half = d // 2
     inv = np.power(np.float64(m.rope_base), -2.0 * np.arange(half) / d)

@@ -137,27 +137,32 @@ def test_argmax_bit_exact(pat, orc):
         assert idx.cpu().tolist() == [orc.argmax_f32(r.numpy()) for r in x]
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("n,k,b", [(256, 1024, 1), (1040, 4096, 16), (512, 5120, 7), (96, 8192, 3), (2048, 256, 16), (4096, 4096, 2),
-                                   (8000, 4096, 5)])
-def test_gemm_with_folded_rmsnorm_vs_oracle(pat, orc, n, k, b):
+                                   (8000, 4096, 5), (1040, 4096, 17), (512, 2752, 32), (4096, 11008, 20)])
+def test_gemm_with_folded_rmsnorm_vs_oracle(pat, orc, n, k, b, fused):
     """The projection of the small-batch step: the operand is x * gains (packed by the producer of x), the rows' sums
     of squares arrive as per-16-column partial sums (what the producing projection writes) and the result is scaled
-    by 1 / rms.  Rows past the live batch are padding and must not leak into any result (NaN here)."""
+    by 1 / rms.  Both kernels that do this: the streaming kernel (up to 32 rows) and the fused layer kernel's
+    projection phase (up to 16).  Rows past the live batch are padding and must not leak into any result (NaN here)."""
+    if fused and b > 16:
+        pytest.skip("the fused layer kernel takes at most 16 rows")
+    R = (b + 15) // 16 * 16
     w, x = _w(n, k, 7 + n + k), _x(b, k, 3 * n + b) * 3.0
     g = pi.normal_bf16(pi.stream_key(1, 3), torch.arange(k, dtype=torch.int64), 0.02, 1.0)
-    x16 = torch.full((16, k), float("nan"))
-    x16[:b] = x
-    stats = (x16.view(16, k // 16, 16) ** 2).sum(-1).T.contiguous()           # [k / 16, 16]
+    xr = torch.full((R, k), float("nan"))
+    xr[:b] = x
+    stats = (xr.view(R, k // 16, 16) ** 2).sum(-1).T.contiguous()             # [k / 16, R]
     wp = pat.pat_op_pack_weight(w.to(DEV))
-    hi, lo = pat.pat_op_pack_act_gain(x16.to(DEV), g.to(DEV))
-    y = pat.pat_op_gemm_norm(wp, n, k, hi, lo, stats.to(DEV), 1e-6, b).cpu().double().numpy()
+    hi, lo = pat.pat_op_pack_act_gain(xr.to(DEV), g.to(DEV))
+    y = pat.pat_op_gemm_norm(wp, n, k, hi, lo, stats.to(DEV), 1e-6, b, fused=fused).cpu().double().numpy()
     assert np.all(np.isfinite(y))
-    for r in sorted(set([0, b - 1, b // 2])):
+    for r in sorted(set([0, b - 1, b // 2, min(b - 1, 15), min(b - 1, 16)])):
         ref = orc.matvec(bits(w), orc.rmsnorm(x[r].double().numpy(), bits(g), 1e-6))
         scale = float(np.sqrt(np.mean(ref * ref)))
         assert np.max(np.abs(y[r] - ref)) <= 1e-4 * scale
     # one part per row (as after the embedding) gives the same 1/rms up to the summation order
-    y1 = pat.pat_op_gemm_norm(wp, n, k, hi, lo, torch.nan_to_num((x16 ** 2).sum(-1), nan=0.0).to(DEV), 1e-6, b)
+    y1 = pat.pat_op_gemm_norm(wp, n, k, hi, lo, torch.nan_to_num((xr ** 2).sum(-1), nan=0.0).to(DEV), 1e-6, b, fused=fused)
     assert np.max(np.abs(y1.cpu().double().numpy() - y)) <= 1e-5 * float(np.sqrt(np.mean(y * y)))
 
 
@@ -175,3 +180,19 @@ def test_embed_stats_rows_sums_and_packed_operand(pat):
     assert np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-30)) <= 2.0 ** -16
     hi2, lo2 = pat.pat_op_pack_act_gain(x[:5].contiguous(), g)                 # the stand-alone packing agrees bit for bit
     assert np.array_equal(pat.unpack_act(hi2, lo2, 5, s.hidden), got)
+
+
+@pytest.mark.parametrize("n,k,b", [(4096, 11008, 20), (4096, 4096, 32), (4096, 4096, 16)])
+def test_projection_is_bitwise_repeatable(pat, n, k, b):
+    """One tile per workgroup, two batch tiles: the case in which a read of a matrix-instruction result that the compiler
+    had moved behind a branch returned a stale element in about one call out of five.  Every sum has a fixed order, so
+    repeated calls must agree bit for bit."""
+    w, x = _w(n, k, 5 + n + k).to(DEV), _x(b, k, 2 * n + b).to(DEV) * 3.0
+    wp = pat.pat_op_pack_weight(w)
+    hi, lo = pat.pat_op_pack_act(x)
+    y0 = torch.empty(b, n, device=DEV)
+    pat.pat_op_gemm(wp, n, k, hi, lo, b, y0, mode=0)
+    for _ in range(60):
+        y = torch.empty(b, n, device=DEV)
+        pat.pat_op_gemm(wp, n, k, hi, lo, b, y, mode=0)
+        assert torch.equal(y, y0)
