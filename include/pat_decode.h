@@ -235,7 +235,8 @@ int pat_step_algo_bytes(pat_ctx *ctx, double *weight_bytes, double *kv_bytes);
 
 /* Kernel-class timing: when enabled, every launch of the class is bracketed by
  * HIP events on the step's stream; totals accumulate until read.
- * class: 0 weight-streaming projections, 1 attention (partial + merge), 2 everything else. */
+ * class: 0 weight-streaming projections other than gate/up (QKV, O, down, vocabulary head; the fused layer launches when
+ * that kernel is in use), 1 attention (partial + merge), 2 everything else, 3 the gate/up projection. */
 int pat_timing_enable(pat_ctx *ctx, int32_t on);
 int pat_timing_read(pat_ctx *ctx, int32_t klass, double *total_ms, int64_t *launches, int32_t reset);
 

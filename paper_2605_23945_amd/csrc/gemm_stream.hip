@@ -117,6 +117,14 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
     // order, a wave folds its pieces per row group with a shuffle butterfly, and the wave sums meet in LDS at the
     // barrier the first tile group has anyway.
     const bool scale = MODE != kGemmAccum && a.sstats != nullptr;     // the residual projections are never the consumer of a norm
+    // requested before the weight stream starts (an idle memory system answers in about a microsecond; behind the
+    // stream the same load waits several), folded after it
+    float4 ssq = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (scale)
+        for (int i = threadIdx.x; i < a.s_parts * PQ; i += kXsWaves * 64) {
+            const float4 t = reinterpret_cast<const float4 *>(a.sstats)[i];
+            ssq.x += t.x; ssq.y += t.y; ssq.z += t.z; ssq.w += t.w;
+        }
     float inv[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) inv[nb] = 1.f;
@@ -140,12 +148,6 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
             k = kown1;
         }
         if (scale && tb0 == rt0) {
-            // (read here, after the streaming loop: held across it, the four sums cost registers the loop has not got)
-            float4 ssq = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int i = threadIdx.x; i < a.s_parts * PQ; i += kXsWaves * 64) {
-                const float4 t = reinterpret_cast<const float4 *>(a.sstats)[i];
-                ssq.x += t.x; ssq.y += t.y; ssq.z += t.z; ssq.w += t.w;
-            }
 #pragma unroll
             for (int off = PQ; off < 64; off <<= 1) {
                 ssq.x += __shfl_xor(ssq.x, off, 64); ssq.y += __shfl_xor(ssq.y, off, 64);

@@ -83,8 +83,8 @@ struct pat_ctx {
     struct Ev { int klass; hipEvent_t a, b; };
     std::vector<Ev> pending;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
-    double t_ms[3] = {0, 0, 0};
-    int64_t t_n[3] = {0, 0, 0};
+    double t_ms[4] = {0, 0, 0, 0};
+    int64_t t_n[4] = {0, 0, 0, 0};
     std::string err;
 };
 
@@ -667,7 +667,7 @@ static int run_layers(pat_ctx *c, int B, int C, int64_t n_chunks, const int32_t 
             GemmArgs g = gemm_args(L + c->wt.wgu, 2 * s.F, s.H, a_hi, a_lo, B, nullptr, 0, gpart, w.gemm_part_bytes);
             g.yhi = b_hi; g.ylo = b_lo; g.KS_out = s.F / 32;
             consume(g, false);
-            TimeScope t(c, 0); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
+            TimeScope t(c, 3); PAT_HIP(c, gemm_groups(g, kGemmSwiGLU, st));
         }
         {
             GemmArgs g = gemm_args(L + c->wt.wd, s.H, s.F, b_hi, b_lo, B, x, s.H, gpart, w.gemm_part_bytes);
@@ -1109,7 +1109,7 @@ int pat_timing_fused_trace(pat_ctx *c, void *trace_dev)
 
 int pat_timing_read(pat_ctx *c, int32_t klass, double *total_ms, int64_t *launches, int32_t reset)
 {
-    if (!c || klass < 0 || klass > 2) return PAT_EINVAL;
+    if (!c || klass < 0 || klass > 3) return PAT_EINVAL;
     int rc = flush_timing(c);
     if (rc) return rc;
     if (total_ms) *total_ms = c->t_ms[klass];
