@@ -98,7 +98,7 @@ typedef struct pat_step_report {
  * kept only if B*L <= T_cap). */
 typedef struct pat_grid_row {
     int32_t tp_degree, batch, kv_len, skipped;   /* skipped: 0 measured, 1 B*L > t_cap, 2 does not fit the pool */
-    int64_t sum_context;                         /* T at the first timed step */
+    int64_t sum_context;                         /* T at the middle of the timed window */
     double  mean_us, min_us, std_us;             /* over reps of the per-rep mean */
     double  tokens_per_s;
     double  algo_bytes;                          /* algorithmic HBM bytes of one step at the window's middle */

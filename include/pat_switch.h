@@ -91,6 +91,26 @@ typedef struct pat_switch_decision {
 
 int pat_switch_decide(const pat_predictor *p, const pat_switch_input *in, pat_switch_decision *out);
 
+/* The offline profiler's sparse sampling plan (Sec. 4.1, "Offline Profiler"): one point per
+ * (TP degree, batch size, context length) with
+ *   - TP degrees 1, 2, 4, 8 up to n_gpus (TP stays inside a node; degrees are powers of two),
+ *   - ten batch sizes spanning [1, 256],
+ *   - context lengths from 8 to l_max (the paper's grid ends at 128K; a pool that holds less ends earlier),
+ *   - a point kept only if batch * length <= t_cap, the deployment's active-token budget,
+ *   - a denser ladder below 512 tokens, where the step latency bends.
+ * The paper fixes these counts and bounds, not the values in between; this library takes
+ *   batch sizes 1, 2, 4, 8, 16, 32, 64, 128, 192, 256 (the octaves, and the middle of the last one, where a
+ *     rollout starts and spends its largest steps),
+ *   lengths 8 * 2^i and, below 512 only, 12 * 2^i as well (two points per octave there, one above).
+ * Points are written in (tp, batch, length) ascending order.  points may be NULL to ask for the count only;
+ * otherwise *n_points holds its capacity on entry.  On return *n_points is the number of points of the plan.
+ * PAT_EINVAL: a NULL n_points, n_gpus < 1, t_cap < 8, l_max < 8; PAT_ENOMEM: capacity too small (nothing
+ * written).  Host only. */
+typedef struct pat_plan_point {
+    int32_t tp_degree, batch, kv_len, reserved;
+} pat_plan_point;
+int pat_profile_plan(int32_t n_gpus, int64_t t_cap, int64_t l_max, pat_plan_point *points, int32_t *n_points);
+
 /* Eq. (1)-(2): seconds to move the valid KV states of the given samples. */
 double pat_kv_move_seconds(const int32_t *lengths, int32_t n, int32_t n_layers, int32_t hidden, int32_t bytes_per_elem,
                            int32_t tp_src, double net_bytes_per_s);

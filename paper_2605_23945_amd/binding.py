@@ -63,6 +63,10 @@ class pat_prefill_row(C.Structure):
     _fields_ = [("tp_degree", C.c_int32), ("batch", C.c_int32), ("length", C.c_int32), ("latency_us", C.c_double)]
 
 
+class pat_plan_point(C.Structure):
+    _fields_ = [("tp_degree", C.c_int32), ("batch", C.c_int32), ("kv_len", C.c_int32), ("reserved", C.c_int32)]
+
+
 class pat_switch_input(C.Structure):
     _fields_ = [("tp", C.c_int32), ("tp_list", C.POINTER(C.c_int32)), ("n_tp", C.c_int32), ("n_gpus", C.c_int32),
                 ("group_batch", C.POINTER(C.c_int32)), ("group_context", C.POINTER(C.c_double)), ("n_groups", C.c_int32),
@@ -84,7 +88,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_la
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
            "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_decode_uses_fused_kernel", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
-           "pat_kv_move_seconds", "pat_rms_length"]
+           "pat_kv_move_seconds", "pat_rms_length", "pat_profile_plan"]
 
 _lib = None
 
@@ -153,6 +157,7 @@ def load_library() -> C.CDLL:
     lib.pat_kv_move_seconds.restype = C.c_double
     lib.pat_rms_length.argtypes = [i32p, C.c_int32]
     lib.pat_rms_length.restype = C.c_double
+    lib.pat_profile_plan.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.POINTER(pat_plan_point), C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -553,3 +558,19 @@ def pat_kv_move_seconds(lengths, n_layers, hidden, bytes_per_elem, tp_src, net_b
 def pat_rms_length(lengths):
     ln = (C.c_int32 * len(lengths))(*[int(x) for x in lengths])
     return load_library().pat_rms_length(ln, len(lengths))
+
+
+def pat_profile_plan(n_gpus, t_cap, l_max, capacity=None):
+    """The offline profiler's sampling plan as a list of (tp_degree, batch, kv_len)."""
+    lib = load_library()
+    n = C.c_int32(0)
+    rc = lib.pat_profile_plan(int(n_gpus), int(t_cap), int(l_max), None, C.byref(n))
+    if rc != 0:
+        raise PatError(rc, "pat_profile_plan: bad arguments")
+    cap = n.value if capacity is None else int(capacity)
+    pts = (pat_plan_point * max(1, cap))()
+    n = C.c_int32(cap)
+    rc = lib.pat_profile_plan(int(n_gpus), int(t_cap), int(l_max), pts, C.byref(n))
+    if rc != 0:
+        raise PatError(rc, "pat_profile_plan: %d points do not fit a capacity of %d" % (n.value, cap))
+    return [(pts[i].tp_degree, pts[i].batch, pts[i].kv_len) for i in range(n.value)]

@@ -117,14 +117,6 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
     // order, a wave folds its pieces per row group with a shuffle butterfly, and the wave sums meet in LDS at the
     // barrier the first tile group has anyway.
     const bool scale = MODE != kGemmAccum && a.sstats != nullptr;     // the residual projections are never the consumer of a norm
-    // requested before the weight stream starts (an idle memory system answers in about a microsecond; behind the
-    // stream the same load waits several), folded after it
-    float4 ssq = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (scale)
-        for (int i = threadIdx.x; i < a.s_parts * PQ; i += kXsWaves * 64) {
-            const float4 t = reinterpret_cast<const float4 *>(a.sstats)[i];
-            ssq.x += t.x; ssq.y += t.y; ssq.z += t.z; ssq.w += t.w;
-        }
     float inv[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) inv[nb] = 1.f;
@@ -147,13 +139,29 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
             }
             k = kown1;
         }
+        // The epilogue's own reads (see EpiPre) travel while the workgroup meets at the barrier.  What the epilogue
+        // derives from the lane index is computed from this copy, which the compiler cannot see through: hoisted
+        // above the stream those values would occupy registers the stream needs (spills inside the loop).
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        EpiPre pre[NB];
+        if (wave < nt) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) pre[nb] = epilogue_prefetch<MODE>(a, tb0 + wave, lane_e >> 4, nb * 16 + (lane_e & 15));
+        }
         if (scale && tb0 == rt0) {
+            // read after the stream, like the epilogue's other operands: nothing of it occupies registers during the stream
+            float4 ssq = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = (wave << 6) + lane_e; i < a.s_parts * PQ; i += kXsWaves * 64) {
+                const float4 t = reinterpret_cast<const float4 *>(a.sstats)[i];
+                ssq.x += t.x; ssq.y += t.y; ssq.z += t.z; ssq.w += t.w;
+            }
 #pragma unroll
             for (int off = PQ; off < 64; off <<= 1) {
                 ssq.x += __shfl_xor(ssq.x, off, 64); ssq.y += __shfl_xor(ssq.y, off, 64);
                 ssq.z += __shfl_xor(ssq.z, off, 64); ssq.w += __shfl_xor(ssq.w, off, 64);
             }
-            if (lane < PQ) *reinterpret_cast<float4 *>(&s_part[wave][lane * 4]) = ssq;
+            if (lane_e < PQ) *reinterpret_cast<float4 *>(&s_part[wave][lane_e * 4]) = ssq;
         }
         __syncthreads();
         if (scale && tb0 == rt0) {
@@ -188,7 +196,7 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
                     }
                 }
                 if (scale) { v.x *= inv[nb]; v.y *= inv[nb]; v.z *= inv[nb]; v.w *= inv[nb]; }
-                gemm_epilogue<MODE>(a, rt, lane >> 4, nb * 16 + (lane & 15), v);
+                gemm_epilogue<MODE>(a, rt, lane_e >> 4, nb * 16 + (lane_e & 15), v, pre[nb]);
             }
         }
         if (tb0 + TB < rt1) __syncthreads();
@@ -342,6 +350,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
                 const int b = (wc * RBT + rb) * 16 + (lane & 15);
                 if (a.Kb == 1) gemm_epilogue<MODE>(a, t0 + ra, lane >> 4, b, v);
                 else store_partial(a, kb, t0 + ra, lane >> 4, b, v);
+                __builtin_amdgcn_sched_barrier(0);      // one tile's epilogue at a time: its reads gathered for all tiles would spill
             }
         }
     }

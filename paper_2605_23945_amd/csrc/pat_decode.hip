@@ -998,6 +998,9 @@ int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32
     hipEvent_t e0, e1;
     PAT_HIP(c, hipEventCreate(&e0));
     PAT_HIP(c, hipEventCreate(&e1));
+    // dummy batches keep their shape for the whole window: a sampled end-of-sequence token ends nothing here
+    const int32_t eos_saved = c->cfg.eos_token;
+    c->cfg.eos_token = -1;
     std::vector<int32_t> ids, toks, lens, tgts;
     int r = 0;
     int rc = PAT_OK;
@@ -1010,9 +1013,10 @@ int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32
             const int total_steps = warmup + steps;
             if (B <= 0 || L < 0) { rc = fail(c, PAT_EINVAL, "profile_grid: batch %d / kv_len %d", B, L); break; }
             if ((int64_t)B * L > t_cap) { row.skipped = 1; continue; }
-            const int64_t pages = (int64_t)B * cdiv(L + total_steps, P);
-            if (B > c->cfg.max_batch || L + total_steps > c->cfg.max_seq_len || pages > s.n_pages ||
-                (int64_t)B * (cdiv(L + total_steps, kMinChunk) + 1) > c->wl.max_chunks) { row.skipped = 2; continue; }
+            // a sequence is admitted with a target of total_steps + 1 tokens, so that none finishes inside the window
+            const int64_t pages = (int64_t)B * cdiv(L + total_steps + 1, P);
+            if (B > c->cfg.max_batch || L + total_steps + 1 > c->cfg.max_seq_len || pages > s.n_pages ||
+                (int64_t)B * (cdiv(L + total_steps + 1, kMinChunk) + 1) > c->wl.max_chunks) { row.skipped = 2; continue; }
             ids.resize(B); toks.resize(B); lens.assign(B, L); tgts.assign(B, total_steps + 1);
             double sum = 0, sum2 = 0, mn = 1e300;
             for (int rep = 0; rep < reps && rc == PAT_OK; ++rep) {
@@ -1022,8 +1026,8 @@ int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32
                 for (int w = 0; w < warmup && rc == PAT_OK; ++w) rc = pat_decode_step(c, nullptr, nullptr, nullptr);
                 if (rc != PAT_OK) break;
                 if (rep == 0) {
-                    row.sum_context = (int64_t)B * (L + warmup);
-                    // algorithmic bytes at the middle of the timed window
+                    // context tokens and algorithmic bytes at the middle of the timed window
+                    row.sum_context = (int64_t)B * (L + warmup + steps / 2);
                     double wb, kb; pat_step_algo_bytes(c, &wb, &kb);
                     const double kv_mid = (double)s.NL * 2 * s.hkv * s.d * 2 * ((double)B * (L + warmup + steps / 2 + 1) + B);
                     row.algo_bytes = wb + kv_mid;
@@ -1044,6 +1048,7 @@ int pat_profile_grid(pat_ctx *c, const int32_t *batches, int32_t nb, const int32
             row.hbm_frac = row.algo_bytes / (row.mean_us * 1e-6) / kHbmPeak;
         }
     (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    c->cfg.eos_token = eos_saved;
     if (rc == PAT_OK) { *n_rows = nb * nl; rc = pat_decode_reset(c); }
     return rc;
 }

@@ -157,6 +157,29 @@ double pat_rms_length(const int32_t *lengths, int32_t n)
     return std::sqrt(s / (double)n);
 }
 
+// Sampling plan of the offline profiler (Sec. 4.1): see the header for the ladder this library takes.
+int pat_profile_plan(int32_t n_gpus, int64_t t_cap, int64_t l_max, pat_plan_point *points, int32_t *n_points)
+{
+    if (!n_points || n_gpus < 1 || t_cap < 8 || l_max < 8) return PAT_EINVAL;
+    static const int32_t kBatches[10] = {1, 2, 4, 8, 16, 32, 64, 128, 192, 256};
+    std::vector<int64_t> lens;
+    for (int64_t base = 8; base <= l_max; base *= 2) {
+        lens.push_back(base);
+        const int64_t mid = base + base / 2;                 // 12 * 2^i: the second point of an octave
+        if (mid < 512 && mid <= l_max) lens.push_back(mid);
+    }
+    std::vector<pat_plan_point> plan;
+    for (int32_t tp = 1; tp <= 8 && tp <= n_gpus; tp *= 2)
+        for (int32_t b : kBatches)
+            for (int64_t L : lens)
+                if ((int64_t)b * L <= t_cap) plan.push_back(pat_plan_point{tp, b, (int32_t)L, 0});
+    const int32_t cap = *n_points;
+    if (points && cap < (int32_t)plan.size()) { *n_points = (int32_t)plan.size(); return PAT_ENOMEM; }
+    if (points) std::copy(plan.begin(), plan.end(), points);
+    *n_points = (int32_t)plan.size();
+    return PAT_OK;
+}
+
 int pat_switch_decide(const pat_predictor *p, const pat_switch_input *in, pat_switch_decision *out)
 {
     if (!p || !in || !out || !in->tp_list || in->n_tp < 1 || in->n_gpus < 1 || in->n_groups < 1 || !in->group_batch ||

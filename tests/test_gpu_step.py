@@ -393,7 +393,7 @@ def test_profile_grid_protocol():
             assert r["skipped"] == 1 and r["mean_us"] == 0.0
         else:
             assert r["skipped"] == 0 and r["mean_us"] > 0 and r["min_us"] <= r["mean_us"]
-            assert r["sum_context"] == b * (l + 2)
+            assert r["sum_context"] == b * (l + 2 + 6)                       # context tokens at the middle of the timed window
             assert abs(r["tokens_per_s"] - b / (r["mean_us"] * 1e-6)) < 1e-6 * r["tokens_per_s"]
             m = shard.model
             wbytes = m.n_layers * 2 * (m.hidden * shard.qkv_rows + shard.hq * m.head_dim * m.hidden + 3 * m.hidden * shard.ffn) \
