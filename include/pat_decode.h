@@ -309,6 +309,16 @@ int pat_op_pack_act_gain(const float *x, const void *g, int32_t b, int32_t k, vo
 int pat_op_gemm_norm(const void *w_packed, int32_t n, int32_t k, const void *xg_hi, const void *xg_lo, const float *stats,
                      int32_t n_parts, float eps, int32_t b, float *y, int32_t ldy, int32_t fused, void *hip_stream);
 int pat_decode_uses_fused_kernel(pat_ctx *ctx);
+/* Cost of the device-wide barrier that the fused layer kernel places between its phases (a measurement aid, no
+ * step of the path): launches n_workgroups workgroups of that kernel's size that do nothing but meet at the
+ * barrier `iters` times, and returns the mean microseconds per barrier (events on the stream; synchronous).
+ * scratch_dev: PAT_BARRIER_PROBE_BYTES of device memory, overwritten.  n_workgroups must not exceed the
+ * device's compute units (all workgroups must be resident at once): PAT_EINVAL otherwise.  Every wait in the
+ * kernel is bounded by max_spin polls; if one runs out, every workgroup still exits and the call returns
+ * PAT_ESTATE with *us_per_barrier untouched. */
+#define PAT_BARRIER_PROBE_BYTES 16384
+int pat_op_barrier_probe(void *scratch_dev, int32_t n_workgroups, int32_t iters, int32_t max_spin,
+                         double *us_per_barrier, void *hip_stream);
 /* (max, lowest index) per row of logits [b, n]; out_idx[b] = base + index. NaN counts as -inf. */
 int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val,
                   void *hip_stream);

@@ -86,7 +86,7 @@ EXPORTS = ["pat_decode_query", "pat_decode_init", "pat_load_layer", "pat_load_la
            "pat_kv_write", "pat_kv_read", "pat_kv_extract", "pat_kv_inject", "pat_prefill", "pat_decode_step", "pat_kv_compact", "pat_get_state", "pat_get_pages",
            "pat_profile_grid", "pat_profile_prefill", "pat_decode_reset", "pat_step_algo_bytes", "pat_timing_enable", "pat_timing_read", "pat_timing_fused_trace",
            "pat_decode_destroy", "pat_last_error", "pat_op_packed_weight_bytes", "pat_op_pack_weight",
-           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_decode_uses_fused_kernel", "pat_op_argmax",
+           "pat_op_packed_act_bytes", "pat_op_pack_act", "pat_op_gemm", "pat_op_gemm_static", "pat_op_gemm_scratch_bytes", "pat_op_gemm_plan", "pat_op_rmsnorm_pack", "pat_op_embed_stats", "pat_op_pack_act_gain", "pat_op_gemm_norm", "pat_decode_uses_fused_kernel", "pat_op_barrier_probe", "pat_op_argmax",
            "pat_predictor_fit", "pat_predictor_destroy", "pat_predictor_line", "pat_predictor_query", "pat_switch_decide",
            "pat_kv_move_seconds", "pat_rms_length", "pat_profile_plan"]
 
@@ -142,6 +142,7 @@ def load_library() -> C.CDLL:
     lib.pat_op_gemm_plan.restype = C.c_int
     lib.pat_op_rmsnorm_pack.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_float, vp, vp, vp]
     lib.pat_op_argmax.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
+    lib.pat_op_barrier_probe.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
     lib.pat_op_embed_stats.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
     lib.pat_op_pack_act_gain.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.pat_op_gemm_norm.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp, C.c_int32, C.c_float, C.c_int32, vp, C.c_int32, C.c_int32, vp]
@@ -459,6 +460,21 @@ def pat_op_argmax(logits, base=0):
     if rc:
         raise PatError(rc, "pat_op_argmax")
     return idx, val
+
+
+PAT_BARRIER_PROBE_BYTES = 16384
+
+
+def pat_op_barrier_probe(n_workgroups, iters=200, max_spin=1 << 22, device="cuda:0"):
+    """Mean microseconds per device-wide barrier among n_workgroups resident workgroups."""
+    import torch
+    lib = load_library()
+    scratch = torch.empty(PAT_BARRIER_PROBE_BYTES, dtype=torch.uint8, device=device)
+    us = C.c_double(0.0)
+    rc = lib.pat_op_barrier_probe(_ptr(scratch), int(n_workgroups), int(iters), int(max_spin), C.byref(us), _stream())
+    if rc:
+        raise PatError(rc, "pat_op_barrier_probe")
+    return us.value
 
 
 def unpack_act(hi, lo, b, k):

@@ -468,6 +468,29 @@ hipError_t launch_pack_act_gain(const float *x, const uint16_t *gains, int b, in
     return hipGetLastError();
 }
 
+// Nothing but the device-wide barrier of the fused layer kernel, `iters` times over: what one barrier costs among
+// n_wg resident workgroups of the fused kernel's size.  A workgroup whose bounded wait runs out sets bit 2 of
+// *err and leaves; the others then run out of theirs: every workgroup exits.
+__global__ __launch_bounds__(kFT) void barrier_probe_kernel(unsigned *sync, int iters, unsigned max_spin, int *err)
+{
+    __shared__ int ok_lds;
+    unsigned gen = 1u;
+    for (int i = 0; i < iters; ++i)
+        if (!grid_sync(sync, gen++, gridDim.x, max_spin, &ok_lds)) {
+            if (threadIdx.x == 0) atomicOr(err, 4);
+            return;
+        }
+}
+
+// sync: kFusedSyncWords zeroed words, then the error word.  n_wg must not exceed the workgroups that are resident
+// at once (checked by the caller against the device's compute units).
+hipError_t launch_barrier_probe(unsigned *sync, int n_wg, int iters, unsigned max_spin, hipStream_t s)
+{
+    if (n_wg <= 0 || iters <= 0) return hipErrorInvalidValue;
+    barrier_probe_kernel<<<n_wg, kFT, 0, s>>>(sync, iters, max_spin, reinterpret_cast<int *>(sync + kFusedSyncWords));
+    return hipGetLastError();
+}
+
 hipError_t launch_sync_reset(unsigned *w, int n_words, hipStream_t s)
 {
     sync_reset_kernel<<<(n_words + 255) / 256, 256, 0, s>>>(w, n_words);

@@ -1276,6 +1276,36 @@ int pat_op_rmsnorm_pack(const float *x, const void *g, int32_t b, int32_t h, flo
     return launch_rmsnorm_pack(x, (const uint16_t *)g, b, h, eps, (uint4 *)xhi, (uint4 *)xlo, (hipStream_t)stream) == hipSuccess ? PAT_OK : PAT_EHIP;
 }
 
+int pat_op_barrier_probe(void *scratch_dev, int32_t n_wg, int32_t iters, int32_t max_spin, double *us_per_barrier, void *stream)
+{
+    if (!scratch_dev || !us_per_barrier || n_wg <= 0 || iters <= 0 || max_spin < 0) return PAT_EINVAL;
+    static_assert((kFusedSyncWords + 1) * sizeof(unsigned) <= PAT_BARRIER_PROBE_BYTES, "probe scratch holds the barrier words and the error word");
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PAT_EHIP;
+    if (n_wg > n_cu) return PAT_EINVAL;                 // one workgroup per compute unit is always resident; more may not be
+    hipStream_t st = (hipStream_t)stream;
+    unsigned *w = (unsigned *)scratch_dev;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return PAT_EHIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return PAT_EHIP; }
+    int rc = PAT_OK;
+    float ms = 0.f;
+    int err = 0;
+    // an untimed launch first (code upload, clocks), then the timed one; the words are zeroed before each
+    for (int pass = 0; pass < 2 && rc == PAT_OK; ++pass) {
+        if (launch_sync_reset(w, kFusedSyncWords + 1, st) != hipSuccess) { rc = PAT_EHIP; break; }
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = PAT_EHIP; break; }
+        if (launch_barrier_probe(w, n_wg, iters, (unsigned)max_spin, st) != hipSuccess) { rc = PAT_EHIP; break; }
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { rc = PAT_EHIP; break; }
+        if (hipMemcpy(&err, w + kFusedSyncWords, sizeof err, hipMemcpyDeviceToHost) != hipSuccess) { rc = PAT_EHIP; break; }
+        if (err != 0) { rc = PAT_ESTATE; break; }
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = PAT_EHIP; break; }
+    }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (rc == PAT_OK) *us_per_barrier = 1e3 * (double)ms / iters;
+    return rc;
+}
+
 int pat_op_argmax(const float *logits, int32_t b, int32_t n, int32_t base, int32_t *out_idx, float *out_val, void *stream)
 {
     if (!logits || !out_idx || b <= 0 || n <= 0) return PAT_EINVAL;

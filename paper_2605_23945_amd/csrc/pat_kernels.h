@@ -118,6 +118,7 @@ hipError_t launch_layer_fused(const FusedArgs &fa, int n_wg, hipStream_t s);
 hipError_t launch_embed_stats(const uint16_t *table, int H, const int32_t *tok, const uint16_t *gains, int B, float *x, float *stats,
                               uint4 *pk_hi, uint4 *pk_lo, hipStream_t s);
 hipError_t launch_pack_act_gain(const float *x, const uint16_t *gains, int b, int k, uint4 *hi, uint4 *lo, hipStream_t s);
+hipError_t launch_barrier_probe(unsigned *sync, int n_wg, int iters, unsigned max_spin, hipStream_t s);
 hipError_t launch_sync_reset(unsigned *w, int n_words, hipStream_t s);
 
 // ---- small kernels (step_misc.hip) ----------------------------------------------

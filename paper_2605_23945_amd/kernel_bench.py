@@ -1,12 +1,13 @@
 """Micro-benchmark of the weight-streaming projection kernels on the shapes of a configuration.
 
     python -m paper_2605_23945_amd.kernel_bench [--config 7b_tp1] [--batch 1,16,32,64,256] [--iters 30]
-                                                 [--only gateup,down,...] [--copy-gib 1]
+                                                 [--only gateup,down,...,barrier] [--copy-gib 1]
 
 Each projection is run on 6 distinct weight copies in rotation (more than the 256 MB
 memory-side cache holds), timed with events on the launch stream.  `--copy-gib` first runs a
 plain device-to-device copy of known size: under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its
-counters calibrate the unit of the projection kernels' counters.
+counters calibrate the unit of the projection kernels' counters.  `--only barrier` times the device-wide barrier
+of the fused layer kernel instead (pat_op_barrier_probe) among 32, 64, 128 and 256 resident workgroups.
 """
 from __future__ import annotations
 
@@ -48,6 +49,16 @@ def main():
         torch.cuda.synchronize()
         print(f"copy  {n} bytes read + {n} bytes written per launch", flush=True)
         del a, b
+    if "barrier" in only:
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        for n_wg in (32, 64, 128, 256):
+            if n_wg > n_cu:
+                continue
+            us = [pat.pat_op_barrier_probe(n_wg, iters=500) for _ in range(3)]
+            print(f"barrier  workgroups={n_wg:4d}  {min(us):6.2f} us per barrier (best of 3 x 500; others {sorted(us)[1]:.2f}, {max(us):.2f})", flush=True)
+        only = [x for x in only if x != "barrier"]
+        if not only:
+            return
     ncopy = max(1, args.copies)
     for name, (n, k, mode) in shapes.items():
         if only and name not in only:

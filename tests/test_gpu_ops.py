@@ -196,3 +196,19 @@ def test_projection_is_bitwise_repeatable(pat, n, k, b):
         y = torch.empty(b, n, device=DEV)
         pat.pat_op_gemm(wp, n, k, hi, lo, b, y, mode=0)
         assert torch.equal(y, y0)
+
+
+def test_device_barrier_probe_runs_and_its_bounded_wait_ends(pat):
+    """The fused layer kernel's device-wide barrier on its own: it completes among resident workgroups, and with a
+    spin limit of zero every workgroup still exits (the call reports the state error instead of hanging)."""
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    for n_wg in (1, 7, min(64, n_cu), n_cu):
+        us = pat.pat_op_barrier_probe(n_wg, iters=50)
+        assert 0.0 < us < 200.0, (n_wg, us)
+    with pytest.raises(pat.PatError) as e:
+        pat.pat_op_barrier_probe(n_cu, iters=4, max_spin=0)        # the host forces the time-out; the kernel ends by itself
+    assert e.value.code == -3
+    with pytest.raises(pat.PatError) as e:
+        pat.pat_op_barrier_probe(n_cu + 1, iters=4)                # more workgroups than are resident at once: refused
+    assert e.value.code == -1
+    assert pat.pat_op_barrier_probe(n_cu, iters=20) > 0.0          # and the next call starts from clean words
