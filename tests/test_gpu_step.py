@@ -494,3 +494,22 @@ def test_per_head_qk_norm_at_live_batch_40_and_the_unsharded_loader():
         outs.append(_gpu_step(dec, 3, shard.vocab)[0])
         dec.close()
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
+def test_optional_fused_layer_kernel_rollout_parity(monkeypatch):
+    """The persistent layer kernel (one launch for merge, O, gate/up, down and the next QKV or the head, with
+    device-wide barriers), which a decoder created under PAT_ENABLE_FUSED=1 takes for live batches <= 16: the same
+    rollout parity as the default path, tokens bit-exact, through compaction down to one sequence."""
+    monkeypatch.setenv("PAT_ENABLE_FUSED", "1")
+    pat = _pat()
+    shard = pi.CONFIGS["tiny_tp1"]["shard"]
+    probe = make_decoder(shard, 4, 64, 400, 16)
+    used = probe.pat_decode_uses_fused_kernel()
+    probe.close()
+    if not used:
+        pytest.skip("the device cannot keep the fused kernel's workgroups resident")
+    targets = [3, 1, 7, 3, 12, 1, 5, 9, 2, 12, 4]
+    worst, steps = _rollout_parity(shard, len(targets), (1, 150), targets, page_tokens=16)
+    assert steps == 12
+    # grouped-query shard with 128-wide heads (the other merge / attention instantiation)
+    _rollout_parity(pi.shard_of(pi.ModelShape(2, 256, 8, 1, 128, 512, 512), 1, 0), 5, (10, 300), [6, 2, 9, 4, 9])
