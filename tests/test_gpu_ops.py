@@ -182,10 +182,12 @@ def test_embed_stats_rows_sums_and_packed_operand(pat):
     assert np.array_equal(pat.unpack_act(hi2, lo2, 5, s.hidden), got)
 
 
-@pytest.mark.parametrize("n,k,b", [(4096, 11008, 20), (4096, 4096, 32), (4096, 4096, 16)])
+@pytest.mark.parametrize("n,k,b", [(4096, 11008, 20), (4096, 4096, 32), (4096, 4096, 16),
+                                   (4096, 11008, 200), (4096, 4096, 64), (12288, 4096, 256), (2048, 8192, 130)])
 def test_projection_is_bitwise_repeatable(pat, n, k, b):
     """One tile per workgroup, two batch tiles: the case in which a read of a matrix-instruction result that the compiler
-    had moved behind a branch returned a stale element in about one call out of five.  Every sum has a fixed order, so
+    had moved behind a branch returned a stale element in about one call out of five.  Above 32 rows: K split across
+    workgroups, the slices' partial sums added in slice order by a second kernel.  Every sum has a fixed order, so
     repeated calls must agree bit for bit."""
     w, x = _w(n, k, 5 + n + k).to(DEV), _x(b, k, 2 * n + b).to(DEV) * 3.0
     wp = pat.pat_op_pack_weight(w)
