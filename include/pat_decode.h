@@ -170,7 +170,8 @@ int pat_kv_inject(pat_ctx *ctx, int32_t n, const int32_t *slots, int32_t layer0,
  * positions in every layer: each token runs through the layers as a row of a ragged batch (rows of
  * several sequences share a pass), attending causally to the positions before it.  The slots'
  * state (last token, lengths) is not changed: the next pat_decode_step continues from the
- * admitted last token.  Waits for the GPU work of every pass (the staging is reused). */
+ * admitted last token.  The passes are enqueued back to back (two host staging sets in turn); the call
+ * returns after the GPU work of the last pass. */
 int pat_prefill(pat_ctx *ctx, int32_t n, const int32_t *slots, const int32_t *tokens, int64_t n_tokens);
 
 /* One decode step over the live batch: embedding, n_layers x (RMSNorm, QKV,

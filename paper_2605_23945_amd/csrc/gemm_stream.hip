@@ -341,15 +341,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
 #undef PAT_XB_TO_LDS
 #undef PAT_XB_FETCH
 
+        // the epilogue's addresses are derived from a copy of the lane index that the compiler cannot see through:
+        // hoisted above the stages they would be spilled there and reloaded here, one dependent round trip each
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
 #pragma unroll
         for (int ra = 0; ra < RA; ++ra) {
             if (ra >= n_live) continue;
 #pragma unroll
             for (int rb = 0; rb < RBT; ++rb) {
                 const float4 v = make_float4(acc[ra][rb][0], acc[ra][rb][1], acc[ra][rb][2], acc[ra][rb][3]);
-                const int b = (wc * RBT + rb) * 16 + (lane & 15);
-                if (a.Kb == 1) gemm_epilogue<MODE>(a, t0 + ra, lane >> 4, b, v);
-                else store_partial(a, kb, t0 + ra, lane >> 4, b, v);
+                const int b = (wc * RBT + rb) * 16 + (lane_e & 15);
+                if (a.Kb == 1) gemm_epilogue<MODE>(a, t0 + ra, lane_e >> 4, b, v);
+                else store_partial(a, kb, t0 + ra, lane_e >> 4, b, v);
                 __builtin_amdgcn_sched_barrier(0);      // one tile's epilogue at a time: its reads gathered for all tiles would spill
             }
         }

@@ -77,7 +77,10 @@ struct pat_ctx {
     unsigned long long *fused_trace = nullptr;   // diagnostics: phase stamps of the fused launches (caller's device buffer)
     // pinned staging
     int32_t *pinned = nullptr;      // 6 * max_batch ints + report
-    int32_t *pf_stage = nullptr;    // pinned: block records of one prefill pass (kPfRecords x 8 ints)
+    int32_t *pf_stage = nullptr;    // pinned, two sets used in turn by the prefill passes: kPfRecords x 8 ints of block
+                                    // records, then 3 * max_batch ints (token, slot, position of the pass's rows)
+    hipEvent_t pf_done[2] = {nullptr, nullptr};   // recorded after the copies that read a set were enqueued
+    bool pf_used[2] = {false, false};
     // timing
     bool timing = false;
     struct Ev { int klass; hipEvent_t a, b; };
@@ -355,11 +358,15 @@ int pat_decode_init(const pat_cfg *cfg, const pat_buffers *bufs, void *hip_strea
     const int MB = cfg->max_batch;
     c->seq_id.resize(MB); c->kv_len.resize(MB); c->gen.resize(MB); c->target.resize(MB); c->fin.assign(MB, 0);
     c->n_free = s.n_pages;
-    auto die = [&](const char *what, hipError_t e) { fprintf(stderr, "pat_decode_init: %s: %s\n", what, hipGetErrorString(e)); if (c->pinned) (void)hipHostFree(c->pinned); if (c->pf_stage) (void)hipHostFree(c->pf_stage); delete c; return PAT_EHIP; };
+    auto die = [&](const char *what, hipError_t e) { fprintf(stderr, "pat_decode_init: %s: %s\n", what, hipGetErrorString(e)); if (c->pinned) (void)hipHostFree(c->pinned); if (c->pf_stage) (void)hipHostFree(c->pf_stage); for (auto ev : c->pf_done) if (ev) (void)hipEventDestroy(ev); delete c; return PAT_EHIP; };
     hipError_t e = hipHostMalloc((void **)&c->pinned, (size_t)(7 * MB + 16) * 4, hipHostMallocDefault);
     if (e != hipSuccess) { c->pinned = nullptr; return die("hipHostMalloc", e); }
-    e = hipHostMalloc((void **)&c->pf_stage, (size_t)kPfRecords * 32, hipHostMallocDefault);
+    e = hipHostMalloc((void **)&c->pf_stage, 2 * ((size_t)kPfRecords * 32 + (size_t)3 * MB * 4), hipHostMallocDefault);
     if (e != hipSuccess) { c->pf_stage = nullptr; return die("hipHostMalloc", e); }
+    for (int i = 0; i < 2; ++i) {
+        e = hipEventCreateWithFlags(&c->pf_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) { c->pf_done[i] = nullptr; return die("hipEventCreate", e); }
+    }
     // rotary table: cos/sin of pos * base^(-2j/d) evaluated in double, stored as fp32 [pos][d/2][2]
     {
         const int half = s.d / 2, npos = cfg->max_seq_len + 1;
@@ -875,13 +882,20 @@ int pat_prefill(pat_ctx *c, int32_t n, const int32_t *slots, const int32_t *toke
     const int MB = c->cfg.max_batch, R_max = MB, C = 256;
     void *W = c->bufs.work;
     int32_t *rows = at<int32_t>(W, c->wl.rows);
-    int32_t *p = c->pinned;
     char *Wb = at<char>(c->bufs.weights, 0);
     int si = 0, pos = 0;
     int64_t t = 0;
     const int NP = 16 / (s.hq / s.hkv);            // positions per attention block (the kernel's 16 operand rows / heads per KV head)
-    int32_t *rec = c->pf_stage;
+    const size_t set_ints = (size_t)kPfRecords * 8 + (size_t)3 * MB;
+    int pass = 0;
     while (t < n_tokens) {
+        // Two pinned staging sets in turn: the host builds pass n + 1 while the GPU runs pass n, and waits only for
+        // the copies that read the set two passes ago.  The device-side row and record buffers are single: the
+        // copies into them are ordered behind the previous pass's kernels on the stream.
+        const int set = pass & 1;
+        if (c->pf_used[set]) PAT_HIP(c, hipEventSynchronize(c->pf_done[set]));
+        int32_t *rec = c->pf_stage + set * set_ints;
+        int32_t *p = rec + (size_t)kPfRecords * 8;
         // one pass: the next rows in (slot, position) order, as many as the work buffers and the
         // attention workspace take; a row's keys are rows of this or an earlier pass.  Rows of one
         // sequence whose positions share pos / NP form a block; a block has one record per chunk of
@@ -913,9 +927,12 @@ int pat_prefill(pat_ctx *c, int32_t n, const int32_t *slots, const int32_t *toke
             PAT_HIP(c, launch_embed_stats((const uint16_t *)(Wb + c->wt.embed), s.H, rows, (const uint16_t *)(Wb + c->wt.layer0 + c->wt.g1), R, at<float>(W, c->wl.x),
                                           at<float>(W, c->wl.stats_e), at<uint4>(W, c->wl.a_hi), at<uint4>(W, c->wl.a_lo), c->stream));
         else PAT_HIP(c, launch_embed((const uint16_t *)(Wb + c->wt.embed), s.H, rows, R, at<float>(W, c->wl.x), c->stream));
+        PAT_HIP(c, hipEventRecord(c->pf_done[set], c->stream));          // the set is free once the copies above have run
+        c->pf_used[set] = true;
         if (int rc = run_layers(c, R, C, chunks, rows + 2 * MB, rows + MB, n_rec)) return rc;
-        PAT_HIP(c, hipStreamSynchronize(c->stream));     // the staging buffers are reused by the next pass
+        ++pass;
     }
+    PAT_HIP(c, hipStreamSynchronize(c->stream));         // the caller's token array is not read after return, and errors surface here
     return PAT_OK;
 }
 
@@ -1131,6 +1148,7 @@ int pat_decode_destroy(pat_ctx *c)
     for (auto &p : c->ev_pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->pf_stage) (void)hipHostFree(c->pf_stage);
+    for (auto ev : c->pf_done) if (ev) (void)hipEventDestroy(ev);
     delete c;
     return PAT_OK;
 }
