@@ -208,7 +208,8 @@ __global__ __launch_bounds__(kXsWaves * 64) void gemm_xs_kernel(GemmArgs a)
 // contiguous range of row tiles x ALL batch tiles x a K slice and walks its rows in chunks of
 // WR * RA tiles.  The waves form a WR x WC grid: a wave keeps RA row tiles x RBT batch tiles of
 // accumulators, takes its weight fragments straight from HBM and the batch tiles' split-bf16
-// fragments from LDS, where one k-step of ALL batch tiles is staged per barrier.
+// fragments from LDS, where a k-step of ALL batch tiles is a stage (one workgroup barrier per stage on
+// the 4- and 8-tile shapes, per two stages on the 12- and 16-tile shapes).
 // Rates per stage that shaped it (CDNA: 128 B/clk of LDS and 64 B/clk of vector memory per compute
 // unit, 16 clk per 16x16x32 matrix instruction and SIMD): a fragment read from LDS must feed at
 // least 4 matrix instructions (RA = 4, both halves), and a wave must request all of a stage's
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
     constexpr int VPT = NV / (NW * 64);
     static_assert(NV % (NW * 64) == 0 && VPT <= 4, "a stage is one to four vectors per thread");
     static_assert(D == 2 || D == 4, "ring of two or four stages");
-    extern __shared__ uint4 xs[];                    // two stages
+    extern __shared__ uint4 xs[];                    // stage buffers: two (D == 4), four (D == 2)
     // the wave index as a scalar: what derives from it (row tiles, fragment bases) stays in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave / WC, wc = wave - wr * WC;
@@ -283,12 +284,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
         if (VPT > 2) st16(dst_ + 2 * (NW * 64) + tid, xr_.v2);                                   \
         if (VPT > 3) st16(dst_ + 3 * (NW * 64) + tid, xr_.v3);                                   \
     }
-// multiply the stage in LDS buffer u_ & 1: its fragments are read in groups of G (high halves first,
+// multiply the stage in LDS buffer number b_: its fragments are read in groups of G (high halves first,
 // then low halves), the next group requested before the current one is multiplied
-#define PAT_XB_MUL(u_, wcur_)                                                                    \
+#define PAT_XB_MUL(b_, wcur_)                                                                    \
     if (n_live > 0) {                                                                            \
         constexpr int G = (RA * RBT >= 32 || RBT % 4) ? 2 : 4, NG = 2 * RBT / G;           \
-        const uint4 *buf = xs + ((u_) & 1) * NV + (wc * RBT) * 64 + lane;                        \
+        const uint4 *buf = xs + (b_) * NV + (wc * RBT) * 64 + lane;                              \
         u32x4_t f[2][G];                                                                         \
         _Pragma("unroll") for (int j = 0; j < G; ++j) f[0][j] = ld16(buf + j * 64);              \
         _Pragma("unroll") for (int g = 0; g < NG; ++g) {                                         \
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
 #define PAT_XB_STAGE(u_, ahead_, xfetch_, wfetch_, wcur_, xnext_)                                \
     {                                                                                            \
         PAT_XB_FETCH(tb + (u_) + (ahead_), xfetch_, wfetch_)                                     \
-        PAT_XB_MUL(u_, wcur_)                                                                    \
+        PAT_XB_MUL((u_) & 1, wcur_)                                                              \
         uint4 *nxt = xs + (((u_) + 1) & 1) * NV;                                                 \
         PAT_XB_TO_LDS(nxt, xnext_)                                                               \
         __syncthreads();                                                                         \
@@ -329,12 +330,48 @@ __global__ __launch_bounds__(NW * 64) void gemm_xb_kernel(GemmArgs a)
                 PAT_XB_STAGE(3, 3, xr2, wq2, wq3, xr0)
             }
         } else {
+            // The 12- and 16-tile shapes (a stage is long enough to cover a load): two stages per barrier.  Four
+            // LDS buffers; the batch fragments of stage t + 2 are requested at the start of stage t and written at
+            // its end (a buffer is rewritten two stages after it was read, with a barrier in between); the weight
+            // fragments wait one stage ahead in two register sets.  Half the workgroup barriers, and half the
+            // times the matrix pipes drain and wait for the first LDS read of a stage: 5-8 % on these shapes.
+#define PAT_XB_FETCH_X(stage_, xr_)                                                              \
+    {                                                                                            \
+        const int ksc_ = min(ks0 + (stage_), ks1 - 1) * 64;                                      \
+        xr_.v0 = ld16(xsrc(0) + ksc_);                                                           \
+        if (VPT > 1) xr_.v1 = ld16(xsrc(1) + ksc_);                                              \
+        if (VPT > 2) xr_.v2 = ld16(xsrc(2) + ksc_);                                              \
+        if (VPT > 3) xr_.v3 = ld16(xsrc(3) + ksc_);                                              \
+    }
+#define PAT_XB_FETCH_W(stage_, wq_)                                                              \
+    {                                                                                            \
+        const int ks_ = ks0 + (stage_);                                                          \
+        const int ksc_ = min(ks_, ks1 - 1) * 64;                                                 \
+        _Pragma("unroll") for (int ra = 0; ra < RA; ++ra) {                                      \
+            const u32x4_t v_ = ld16(wsrc[ra] + ksc_ + lane);                                     \
+            wq_[ra] = (ks_ < ks1 && ra < n_live) ? v_ : zero_v;                                  \
+        }                                                                                        \
+    }
+            PAT_XB_FETCH_X(0, xr0)
+            PAT_XB_FETCH_X(1, xr1)
+            PAT_XB_FETCH_W(0, wq0)
             PAT_XB_TO_LDS(xs, xr0)
+            PAT_XB_TO_LDS(xs + NV, xr1)
             __syncthreads();
             for (int tb = 0; tb < n_stage; tb += 2) {
-                PAT_XB_STAGE(0, 1, xr1, wq1, wq0, xr1)
-                PAT_XB_STAGE(1, 1, xr0, wq0, wq1, xr0)
+                const int p = tb & 2;                                      // buffers of this pair of stages: p, p + 1
+                PAT_XB_FETCH_X(tb + 2, xr0)
+                PAT_XB_FETCH_W(tb + 1, wq1)
+                PAT_XB_MUL(p, wq0)
+                PAT_XB_TO_LDS(xs + (p ^ 2) * NV, xr0)
+                PAT_XB_FETCH_X(tb + 3, xr1)
+                PAT_XB_FETCH_W(tb + 2, wq0)
+                PAT_XB_MUL(p + 1, wq1)
+                PAT_XB_TO_LDS(xs + ((p ^ 2) + 1) * NV, xr1)
+                __syncthreads();
             }
+#undef PAT_XB_FETCH_X
+#undef PAT_XB_FETCH_W
         }
 #undef PAT_XB_MUL
 #undef PAT_XB_STAGE
@@ -509,11 +546,23 @@ hipError_t launch_xs(const GemmArgs &a, int mode, hipStream_t s)
     return hipGetLastError();
 }
 
+// the four stage buffers of the 12- and 16-tile shapes exceed the default limit of dynamic LDS
+template <int NW, int WC, int RBT, int RA, int D>
+hipError_t xb_set_lds_limit()
+{
+    constexpr int lds = (D == 2 ? 4 : 2) * 2 * WC * RBT * 64 * (int)sizeof(uint4);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmStore>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmAccum>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmSwiGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmQKV>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e;
+}
+
 template <int NW, int WC, int RBT, int RA, int D>
 hipError_t launch_xb(const GemmArgs &a, int mode, hipStream_t s)
 {
     const dim3 grid(a.Rg, a.Kb);
-    constexpr size_t lds = (size_t)2 * 2 * WC * RBT * 64 * sizeof(uint4);
+    constexpr size_t lds = (size_t)(D == 2 ? 4 : 2) * 2 * WC * RBT * 64 * sizeof(uint4);
     switch (mode) {
     case kGemmStore: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmStore><<<grid, NW * 64, lds, s>>>(a); break;
     case kGemmAccum: gemm_xb_kernel<NW, WC, RBT, RA, D, kGemmAccum><<<grid, NW * 64, lds, s>>>(a); break;
@@ -537,6 +586,8 @@ hipError_t gemm_prepare_device()
     if (dev >= 0 && dev < 64 && (done >> dev & 1)) return hipSuccess;
     e = xs_set_lds_limit<1, 8, 8, 16>();
     if (e == hipSuccess) e = xs_set_lds_limit<2, 8, 8, 8>();
+    if (e == hipSuccess) e = xb_set_lds_limit<8, 2, 6, 4, 2>();
+    if (e == hipSuccess) e = xb_set_lds_limit<8, 2, 8, 4, 2>();
     if (e == hipSuccess && dev >= 0 && dev < 64) done |= 1ull << dev;
     return e;
 }
@@ -595,7 +646,7 @@ hipError_t launch_gemm(const GemmArgs &a0, int mode, hipStream_t s)
     if (a.ngains != nullptr && (a.n_valid % 32 != 0 || !a.npk_hi || !a.npk_lo || !a.nstats)) return hipErrorInvalidValue;
     if (a.Kb > 1 && (a.part == nullptr || (int64_t)a.Kb * a.B * a.n_tiles * 64 > a.part_bytes)) return hipErrorInvalidValue;
     // measured on MI355X: 16 waves x 8 resident k-steps is best for one batch tile, 8 x 8 for two
-    if (a.B <= 32) { const hipError_t e = gemm_prepare_device(); if (e != hipSuccess) return e; }
+    { const hipError_t e = gemm_prepare_device(); if (e != hipSuccess) return e; }
     if (a.B <= 16) return launch_xs<1, 8, 8, 16>(a, mode, s);
     if (a.B <= 32) return launch_xs<2, 8, 8, 8>(a, mode, s);
     const hipError_t e = p.NB == 4 ? launch_xb<8, 1, 4, 2, 4>(a, mode, s)
